@@ -1,0 +1,246 @@
+"""Invariants of the CPU oracle's environment step (CPU only).  Each one follows from a statement
+of the paper's MDP and would be broken by a plausible slip (wrong sign, wrong position, stale
+cache, off-by-one in the window)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2408_12525_amd import workloads as wl
+
+
+def small(problem, **kw):
+    d = dict(batch=6, size=8, obs_w=7, max_steps=50)
+    d.update(kw)
+    return wl.make_config(problem, d.pop("batch"), d.pop("size"), d.pop("obs_w"), **d)
+
+
+def run(cfg, steps, seed=3, aseed=9, bad=0.0):
+    env = oracle.Oracle(cfg)
+    obs0 = env.reset(seed)
+    acts = wl.random_actions(cfg, aseed, steps, bad)
+    return env, obs0, acts
+
+
+def loss_vec(cfg, m):
+    lo = np.array(cfg["target_lo"][:m.shape[-1]])
+    hi = np.array(cfg["target_hi"][:m.shape[-1]])
+    return np.maximum(0, np.maximum(lo - m, m - hi))
+
+
+@pytest.mark.parametrize("problem", [wl.BINARY, wl.MAZE, wl.DUNGEON])
+def test_rewards_telescope_to_the_loss_drop(problem):
+    # reward = decrease of the loss each step  =>  sum over an episode = loss(start) - loss(end)
+    cfg = small(problem, autoreset=0, max_steps=10**6)
+    env, _, acts = run(cfg, 120)
+    M = env.M
+    w = np.array(cfg["weights"][:M], np.float64)
+    l0 = loss_vec(cfg, env.metrics())
+    total = np.zeros(env.B)
+    for a in acts:
+        _, r, _ = env.step(a, want_obs=False)
+        total += r
+    lT = loss_vec(cfg, env.metrics())
+    assert np.array_equal(total, ((l0 - lT) * w).sum(axis=1))   # integer weights: exact
+
+
+@pytest.mark.parametrize("problem", [wl.BINARY, wl.MAZE, wl.DUNGEON])
+def test_cached_metrics_equal_a_fresh_recount(problem):
+    cfg = small(problem, min_size=4, n_frozen=2)
+    env, _, acts = run(cfg, 60)
+    for a in acts:
+        env.step(a, want_obs=False)
+        st = env.get_state()
+        m = env.metrics()
+        for b in range(env.B):
+            h, w = st["hw"][b]
+            assert (oracle.level_metrics(problem, st["tiles"][b, :h, :w]) == m[b]).all()
+            assert m[b, -env.K:].sum() == h * w                  # counts cover the active map
+
+
+def test_noop_and_frozen_edits_change_nothing_and_pay_nothing():
+    cfg = small(wl.MAZE, n_frozen=4, pos_mode=wl.POS_SCAN, size=5, obs_w=3, autoreset=0,
+                max_steps=10**6)
+    env = oracle.Oracle(cfg)
+    env.reset(1)
+    for t in range(75):
+        st = env.get_state()
+        py, px = st["pos"][:, 0], st["pos"][:, 1]
+        cur = st["tiles"][np.arange(env.B), py, px]
+        fro = st["frozen"][np.arange(env.B), py, px].astype(bool)
+        a = ((cur + 1 + t % 3) % 4).astype(np.int32)             # always a different tile
+        a[::2] = cur[::2]                                        # even envs: same tile (no-op)
+        m0 = env.metrics()
+        _, r, _ = env.step(a, want_obs=False)
+        st1 = env.get_state()
+        same = (st1["tiles"] == st["tiles"]).all(axis=(1, 2))
+        must_noop = fro | (a == cur)
+        assert (same == must_noop).all()
+        assert (r[must_noop] == 0).all()
+        assert (env.metrics()[must_noop] == m0[must_noop]).all()
+        assert (st1["frozen"] == st["frozen"]).all()
+        assert (st1["counters"][:, 1] - st["counters"][:, 1] == (~must_noop)).all()
+    assert (st["frozen"].sum(axis=(1, 2)) == 4).all()
+
+
+def test_out_of_range_actions_are_noops():
+    cfg = small(wl.BINARY, autoreset=0)
+    env, _, _ = run(cfg, 1)
+    for bad in (-1, 2, 99, -2**31):
+        before = env.get_state()["tiles"].copy()
+        _, r, _ = env.step(np.full(env.B, bad, np.int32), want_obs=False)
+        assert (env.get_state()["tiles"] == before).all() and (r == 0).all()
+
+
+def numpy_window(tiles, h, w, py, px, ow, K, pad_border):
+    """Independent formulation: pad the active map, slice, one-hot with an identity matrix."""
+    r = ow // 2
+    pad_val = K if pad_border else 1
+    t = np.pad(tiles[:h, :w].astype(np.int64), ow, constant_values=pad_val)
+    win = t[py + ow - r: py + ow - r + ow, px + ow - r: px + ow - r + ow]
+    C = K + (1 if pad_border else 0)
+    return np.eye(C, dtype=np.uint8)[win].transpose(2, 0, 1)
+
+
+@pytest.mark.parametrize("problem,ow,pad", [(wl.BINARY, 31, wl.PAD_WALL), (wl.MAZE, 31, wl.PAD_BORDER),
+                                            (wl.BINARY, 3, wl.PAD_BORDER), (wl.DUNGEON, 15, wl.PAD_BORDER),
+                                            (wl.BINARY, 63, wl.PAD_BORDER), (wl.MAZE, 8, wl.PAD_BORDER)])
+def test_observation_is_the_padded_onehot_window_at_the_new_position(problem, ow, pad):
+    cfg = wl.make_config(problem, 5, 16, ow, min_size=6, pad_mode=pad, max_steps=40)
+    env, obs, acts = run(cfg, 45)
+    K = env.K
+    for t in range(len(acts) + 1):
+        st = env.get_state()
+        for b in range(env.B):
+            h, w = st["hw"][b]
+            py, px = st["pos"][b]
+            want = numpy_window(st["tiles"][b], h, w, py, px, ow, K, pad == wl.PAD_BORDER)
+            assert (obs[b] == want).all()
+            assert (obs[b].sum(axis=0) == 1).all()                       # one-hot everywhere
+            r = ow // 2
+            assert obs[b, st["tiles"][b, py, px], r, r] == 1            # centre = agent's tile
+            if pad == wl.PAD_BORDER and ow >= 31:
+                assert obs[b, :K].sum() == h * w                         # global view: whole map
+        if t < len(acts):
+            obs, _, _ = env.step(acts[t])
+
+
+def test_scan_visits_every_cell_once_per_sweep():
+    cfg = wl.make_config(wl.BINARY, 4, 9, 3, min_size=3, pos_mode=wl.POS_SCAN, autoreset=0,
+                         max_steps=10**6)
+    env = oracle.Oracle(cfg)
+    env.reset(5)
+    st = env.get_state()
+    assert (st["pos"] == 0).all()
+    hw = st["hw"].astype(int)
+    seen = [dict() for _ in range(env.B)]
+    for t in range(2 * 81):
+        pos = env.get_state()["pos"]
+        for b in range(env.B):
+            seen[b].setdefault(tuple(pos[b]), []).append(t)
+        env.step(np.zeros(env.B, np.int32), want_obs=False)
+    for b in range(env.B):
+        h, w = hw[b]
+        assert set(seen[b]) == {(y, x) for y in range(h) for x in range(w)}
+        for (y, x), ts in seen[b].items():
+            assert ts[0] == y * w + x and all(t2 - t1 == h * w for t1, t2 in zip(ts, ts[1:]))
+
+
+def test_done_fires_at_max_steps_and_autoreset_starts_a_new_seeded_episode():
+    cfg = small(wl.MAZE, max_steps=7, min_size=4)
+    env, _, acts = run(cfg, 30)
+    ref = oracle.Oracle(cfg)       # a second oracle reproduces the episodes' first levels
+    for t, a in enumerate(acts, 1):
+        _, r, d = env.step(a, want_obs=False)
+        assert (d == (t % 7 == 0)).all()
+        st = env.get_state()
+        assert (st["counters"][:, 0] == t % 7).all()
+        assert (st["counters"][:, 2] == t // 7).all()
+    # without autoreset done stays up and the level is kept
+    cfg2 = small(wl.MAZE, max_steps=7, autoreset=0)
+    env2, _, acts2 = run(cfg2, 12)
+    for t, a in enumerate(acts2, 1):
+        _, _, d = env2.step(a, want_obs=False)
+        assert (d == (t >= 7)).all()
+    assert (env2.get_state()["counters"][:, 2] == 0).all()
+    del ref
+
+
+def test_change_budget_ends_the_episode():
+    cfg = small(wl.BINARY, max_changes=3, max_steps=10**6, autoreset=0, pos_mode=wl.POS_SCAN)
+    env = oracle.Oracle(cfg)
+    env.reset(2)
+    for _ in range(40):
+        st = env.get_state()
+        cur = st["tiles"][np.arange(env.B), st["pos"][:, 0], st["pos"][:, 1]]
+        _, _, d = env.step((1 - cur).astype(np.int32), want_obs=False)     # always flips
+        n = env.get_state()["counters"][:, 1]
+        assert (d == (n >= 3)).all()
+
+
+def test_reset_is_a_pure_function_of_seed_and_env_index():
+    cfg = small(wl.DUNGEON, batch=8, min_size=4, n_frozen=3)
+    a, b = oracle.Oracle(cfg), oracle.Oracle(cfg)
+    oa, ob = a.reset(42), b.reset(42)
+    assert (oa == ob).all()
+    sa, sb = a.get_state(), b.get_state()
+    assert all((sa[k] == sb[k]).all() for k in sa)
+    oc = b.reset(43)
+    assert not (oc == oa).all()
+    # env i of a batch of 8 equals env i of a batch of 3 (keys use the global env index)
+    c = oracle.Oracle(dict(cfg, batch=3))
+    c.reset(42)
+    sc = c.get_state()
+    assert all((sc[k] == sa[k][:3]).all() for k in sc)
+
+
+def test_shapes_pinpoints_and_tiles_follow_the_configured_distributions():
+    cfg = wl.workload("binary32_rand_ow3", batch=6000)
+    env = oracle.Oracle(cfg)
+    env.reset(0, want_obs=False)
+    st = env.get_state()
+    hw = st["hw"].astype(int)
+    assert hw.min() == 8 and hw.max() == 32
+    for axis in (0, 1):
+        cnt = np.bincount(hw[:, axis], minlength=33)[8:]
+        exp = 6000 / 25
+        assert ((cnt - exp) ** 2 / exp).sum() < 60          # chi-square, 24 dof (p ~ 1e-4)
+    inside = st["tiles"] >= 0
+    assert (inside.sum(axis=(1, 2)) == hw[:, 0] * hw[:, 1]).all()
+    for b in range(0, 6000, 97):                              # top-left anchored rectangle
+        h, w = hw[b]
+        assert inside[b, :h, :w].all() and not inside[b, h:].any() and not inside[b, :, w:].any()
+    assert (st["frozen"].sum(axis=(1, 2)) == 3).all()
+    assert not (st["frozen"].astype(bool) & ~inside).any()
+    walls = (st["tiles"] == 1).sum() / inside.sum()
+    assert abs(walls - 0.5) < 0.002
+    # dungeon tile frequencies
+    cfg = wl.workload("dungeon32", batch=200)
+    env = oracle.Oracle(cfg)
+    env.reset(1, want_obs=False)
+    t = env.get_state()["tiles"]
+    freq = np.bincount(t.ravel(), minlength=7) / t.size
+    assert np.abs(freq - np.array([.4, .4, .04, .04, .04, .04, .04])).max() < 0.003
+    # empty start
+    cfg = wl.make_config(wl.MAZE, 3, 8, 5, probs="empty")
+    env = oracle.Oracle(cfg)
+    env.reset(1, want_obs=False)
+    assert (env.get_state()["tiles"] == 0).all()
+
+
+def test_set_state_installs_a_level_and_recomputes_metrics():
+    import levels
+    problem, tiles, expect = levels.load("maze_detour_3x5.txt")
+    cfg = wl.make_config(wl.MAZE, 2, 8, 5, min_size=3, autoreset=0)
+    env = oracle.Oracle(cfg)
+    env.reset(0)
+    buf = np.full((2, 8, 8), -1, np.int8)
+    buf[:, :3, :5] = tiles
+    env.set_state(buf, None, np.array([[3, 5], [3, 5]]), np.array([[0, 1], [2, 3]]))
+    m = env.metrics()
+    assert m[0, 0] == expect["regions"] and m[0, 1] == expect["path"]
+    # removing the wall next to the player opens a short cut: path 8 -> 4
+    _, r, _ = env.step(np.array([0, 1], np.int32), want_obs=False)
+    m2 = env.metrics()
+    assert m2[0, 1] == 4 and r[0] == 2.0 * (4 - 8)
+    # env 1 walls off (2,3)... already a wall: no-op
+    assert r[1] == 0 and (m2[1] == m[1]).all()
