@@ -1,0 +1,175 @@
+/*
+ * pcgrl.h -- C ABI of the MI355X (gfx950) batched PCGRL environment step.
+ *
+ * One context owns a batch of level-editing environments resident in GPU memory.  Each call to
+ * pcgrl_step applies one tile edit per level, recomputes that level's region / path metrics and
+ * tile counts, turns the change of the distance-to-target into a float32 reward, moves the agent
+ * on and writes its egocentric, padded one-hot observation (paper: Methods / Training and
+ * Methods / Task).  Nothing here allocates per call, synchronises, or touches host copies of the
+ * per-environment arrays.
+ *
+ * Conventions for every entry point
+ *   - Return value: PCGRL_OK (0) or a negative PCGRL_E_* code; no exceptions, no aborts.
+ *     pcgrl_strerror() names a code.
+ *   - "device pointer" = memory on the context's GPU, owned by the caller (for example a PyTorch
+ *     tensor's data_ptr()); the library never frees it and never keeps it after the call's
+ *     kernels have run.  "host pointer" = ordinary process memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued on
+ *     it and the call returns without waiting, unless stated otherwise.
+ *   - Calls on one context must be ordered by the caller (same stream, or events).
+ *
+ * Tile ids.  binary: 0 empty, 1 wall.  maze: 0 empty, 1 wall, 2 player, 3 door.
+ *            dungeon: 0 empty, 1 wall, 2 player, 3 key, 4 door, 5 enemy, 6 chest.
+ * Every tile except wall can be walked on and belongs to a region.
+ *
+ * Metric vector (int32, M entries per environment):
+ *   [0] regions   number of 4-connected components of walkable cells   (Task / Binary domain)
+ *   [1] path      binary : two-sweep diameter estimate of the component of the first walkable
+ *                          cell in row-major order                      (Binary domain, footnote)
+ *                 maze   : shortest player -> door distance            (Task / Maze domain)
+ *                 dungeon: shortest player -> key -> door distance     (Task / Dungeon domain)
+ *   [2] nearest enemy distance from the player (dungeon only)           (Task / Dungeon domain)
+ *   then the count of each tile id 0..K-1 inside the active map.
+ *   M = 4 (binary), 6 (maze), 10 (dungeon).  Distances count edges; a quantity that does not
+ *   exist (no source, no destination, no connection) is 0.
+ */
+#ifndef PCGRL_H
+#define PCGRL_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PCGRL_OK 0
+#define PCGRL_E_NULL (-1)     /* a required pointer is NULL */
+#define PCGRL_E_CONFIG (-2)   /* a configuration field is out of range */
+#define PCGRL_E_HIP (-3)      /* a HIP runtime call failed */
+#define PCGRL_E_NOMEM (-4)    /* device allocation failed */
+#define PCGRL_E_DEVICE (-5)   /* the device is not a gfx950 part or does not exist */
+
+#define PCGRL_BINARY 0
+#define PCGRL_MAZE 1
+#define PCGRL_DUNGEON 2
+
+#define PCGRL_PAD_BORDER 0 /* cells outside the map set an extra channel K (Discussion: border tiles) */
+#define PCGRL_PAD_WALL 1   /* cells outside the map read as wall */
+
+#define PCGRL_POS_SCAN 0   /* row-major scan of the active map, wrapping (Methods / Training) */
+#define PCGRL_POS_RANDOM 1 /* seeded uniform position every step */
+
+#define PCGRL_REGIONS_INCREMENTAL 0 /* update the region count from floods around the edited cell */
+#define PCGRL_REGIONS_RECOUNT 1     /* flood every component again after each modifying edit */
+
+#define PCGRL_MAX_METRICS 16
+#define PCGRL_MAX_TILES 8
+
+typedef struct pcgrl_ctx pcgrl_ctx; /* opaque; owns its device state */
+
+typedef struct {
+  int32_t problem;      /* PCGRL_BINARY / MAZE / DUNGEON                     (Methods / Task) */
+  int32_t batch;        /* number of environments, >= 1 */
+  int32_t max_h, max_w; /* buffer that holds every map shape, each in 1..64 */
+  int32_t min_h, min_w; /* equal to max_* for a fixed shape; otherwise height and width are drawn
+                           uniformly and independently in [min, max] at the start of every episode
+                           and the map sits in the top-left corner (Task / Randomized map shapes) */
+  int32_t obs_w;        /* side of the observation window, 1..63; the agent's cell is cell
+                           (obs_w/2, obs_w/2) of the window             (Methods / Training) */
+  int32_t pad_mode;     /* PCGRL_PAD_* */
+  int32_t pos_mode;     /* PCGRL_POS_* */
+  int32_t n_frozen;     /* pinpoint cells per episode, 0..8: distinct seeded cells of the active
+                           map that keep their initial tile                (Task / Pinpoint tiles) */
+  int32_t max_steps;    /* >= 1; done when the episode's step count reaches it */
+  int32_t max_changes;  /* 0 = off; otherwise done when that many edits modified the map */
+  int32_t autoreset;    /* non-zero: a finished episode is replaced by a fresh seeded one inside
+                           the same step; reward and done describe the finished transition, the
+                           observation and cached metrics the new episode's first state */
+  int32_t regions_mode; /* PCGRL_REGIONS_*; both give the same counts */
+  uint32_t init_cdf[PCGRL_MAX_TILES]; /* non-decreasing cumulative tile probabilities scaled by
+                           2^32 (entry k = P(tile <= k)); the last tile takes the rest; all zero =
+                           start from an all-empty map                      (Methods / Task) */
+  float weights[PCGRL_MAX_METRICS];     /* reward weight of each metric      (Methods / Training) */
+  int32_t target_lo[PCGRL_MAX_METRICS]; /* default target range of each metric; the loss of a */
+  int32_t target_hi[PCGRL_MAX_METRICS]; /* metric v is max(0, lo - v, v - hi) */
+} pcgrl_config;
+
+/* Fills *cfg with this library's defaults for a problem: fixed 16x16 map, window 31, border
+ * padding, scan order, no pinpoints, 1000 steps, autoreset, uniform initial tiles, and the reward
+ * table (one region, path as long as possible, one player / key / door, 2..5 enemies, nearest
+ * enemy >= 4).  cfg: host pointer. */
+int pcgrl_config_default(int32_t problem, pcgrl_config* cfg);
+
+/* Creates a context on GPU `device` and allocates all device state (about
+ * 3*S*8 + 230 bytes per environment, S = 16, 32 or 64 covering max_h and max_w).  The
+ * environments start as if pcgrl_reset(seed = 0) had been called.  Synchronises.
+ * cfg, out: host pointers.  Errors: E_NULL, E_CONFIG, E_DEVICE, E_NOMEM, E_HIP. */
+int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device);
+
+/* Frees the context and its device memory.  Synchronises the device first.  NULL is accepted. */
+int pcgrl_destroy(pcgrl_ctx* ctx);
+
+/* Starts episode 0 of every environment from `seed`: shape, tiles, pinpoints, first position
+ * (all from a counter-based generator keyed by seed, global environment index and episode, so
+ * results do not depend on batch size), default target ranges, full metrics.
+ * obs: device pointer, uint8 [batch][C][obs_w][obs_w], or NULL to skip the observation. */
+int pcgrl_reset(pcgrl_ctx* ctx, uint64_t seed, uint8_t* obs, void* stream);
+
+/* One environment step for the whole batch (Methods / Training; Methods / Task).
+ *   actions: device, int32 [batch]; the tile to write at the agent's cell.  A value outside
+ *            0..K-1 is a no-op edit (counted, see pcgrl_bad_action_count); so is writing the tile
+ *            already there or writing to a frozen cell.
+ *   obs    : device, uint8 [batch][C][obs_w][obs_w], planar one-hot window centred on the agent's
+ *            NEW cell; C = K, plus 1 under PCGRL_PAD_BORDER.  May be NULL.
+ *   reward : device, float32 [batch]: sum over metrics, in index order, of
+ *            weight * (loss before - loss after); exactly 0 when the edit was a no-op.
+ *   done   : device, uint8 [batch].
+ * reward and done may be NULL. */
+int pcgrl_step(pcgrl_ctx* ctx, const int32_t* actions, uint8_t* obs, float* reward, uint8_t* done,
+               void* stream);
+
+/* Copies the cached metric vectors.  out: device, int32 [batch][M]. */
+int pcgrl_metrics(pcgrl_ctx* ctx, int32_t* out, void* stream);
+
+/* Writes the current observation of every environment without stepping.  obs: device. */
+int pcgrl_observe(pcgrl_ctx* ctx, uint8_t* obs, void* stream);
+
+/* Reads the environments back in a plain layout (all device pointers, any may be NULL):
+ *   tiles int8 [batch][max_h][max_w] (-1 outside the active map), frozen uint8 same shape,
+ *   hw int16 [batch][2], pos int16 [batch][2], counters int32 [batch][3] = step count,
+ *   modifying edits, episode number. */
+int pcgrl_get_state(pcgrl_ctx* ctx, int8_t* tiles, uint8_t* frozen, int16_t* hw, int16_t* pos,
+                    int32_t* counters, void* stream);
+
+/* Installs levels chosen by the caller -- the designer-placed layouts of Task / Pinpoint tiles.
+ * Same layouts as pcgrl_get_state; frozen may be NULL (nothing frozen), the rest is required.
+ * Cells outside hw are ignored; a tile id outside 0..K-1 is stored as empty; hw and pos are
+ * clamped into range.  Step and change counters restart at 0, targets are kept, metrics are
+ * recomputed from scratch. */
+int pcgrl_set_state(pcgrl_ctx* ctx, const int8_t* tiles, const uint8_t* frozen, const int16_t* hw,
+                    const int16_t* pos, void* stream);
+
+/* Per-environment target ranges (control targets of Methods / Training).
+ * targets: device, int32 [batch][M][2] = (lo, hi).  They stay in force until the next
+ * pcgrl_reset, which restores the configuration's defaults. */
+int pcgrl_set_targets(pcgrl_ctx* ctx, const int32_t* targets, void* stream);
+
+/* Shape queries (host side, no GPU work).  out: host pointer to 4 ints = batch, C, obs_w, obs_w. */
+int pcgrl_obs_shape(const pcgrl_ctx* ctx, int32_t out[4]);
+int pcgrl_num_metrics(const pcgrl_ctx* ctx);
+int pcgrl_num_tiles(const pcgrl_ctx* ctx);
+
+/* Number of out-of-range actions seen since creation.  Waits for `stream`.  out: host pointer. */
+int pcgrl_bad_action_count(pcgrl_ctx* ctx, uint64_t* out, void* stream);
+
+/* Checks on the GPU that the cross-lane row exchange used by the flood kernels moves data the way
+ * the kernels assume (each of the 3 lane groupings, both directions).  Synchronises.
+ * mismatches: host pointer, receives the number of lanes that disagreed (0 = good). */
+int pcgrl_selftest(int device, int32_t* mismatches);
+
+const char* pcgrl_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,217 @@
+"""Thin Python binding of the C ABI in include/pcgrl.h.
+
+Argument marshalling only: tensors are checked (device, dtype, shape, contiguity) and handed over
+as raw device pointers together with the current HIP stream.  Every step of the environment runs
+in the library's kernels.  There is no fallback: if the compiled library is missing or cannot be
+loaded, the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+from . import build as _build
+
+MAX_METRICS, MAX_TILES = 16, 8
+
+
+class PcgrlConfig(C.Structure):
+    _fields_ = [
+        ("problem", C.c_int32), ("batch", C.c_int32),
+        ("max_h", C.c_int32), ("max_w", C.c_int32),
+        ("min_h", C.c_int32), ("min_w", C.c_int32),
+        ("obs_w", C.c_int32), ("pad_mode", C.c_int32), ("pos_mode", C.c_int32),
+        ("n_frozen", C.c_int32), ("max_steps", C.c_int32), ("max_changes", C.c_int32),
+        ("autoreset", C.c_int32), ("regions_mode", C.c_int32),
+        ("init_cdf", C.c_uint32 * MAX_TILES),
+        ("weights", C.c_float * MAX_METRICS),
+        ("target_lo", C.c_int32 * MAX_METRICS),
+        ("target_hi", C.c_int32 * MAX_METRICS),
+    ]
+
+
+EXPORTS = [
+    "pcgrl_config_default", "pcgrl_create", "pcgrl_destroy", "pcgrl_reset", "pcgrl_step",
+    "pcgrl_metrics", "pcgrl_observe", "pcgrl_get_state", "pcgrl_set_state", "pcgrl_set_targets",
+    "pcgrl_obs_shape", "pcgrl_num_metrics", "pcgrl_num_tiles", "pcgrl_bad_action_count",
+    "pcgrl_selftest", "pcgrl_strerror",
+]
+
+_lib = None
+
+
+class PcgrlError(RuntimeError):
+    pass
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def load():
+    """Loads the in-tree library (never builds it); raises if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        raise PcgrlError(f"{path} is missing: build it first (python -m paper_2408_12525_amd.build); "
+                         "there is no fallback implementation")
+    L = C.CDLL(path)
+    p, i32, u64 = C.c_void_p, C.c_int32, C.c_uint64
+    L.pcgrl_config_default.argtypes = [i32, C.POINTER(PcgrlConfig)]
+    L.pcgrl_create.argtypes = [C.POINTER(p), C.POINTER(PcgrlConfig), C.c_int]
+    L.pcgrl_destroy.argtypes = [p]
+    L.pcgrl_reset.argtypes = [p, u64, p, p]
+    L.pcgrl_step.argtypes = [p, p, p, p, p, p]
+    L.pcgrl_metrics.argtypes = [p, p, p]
+    L.pcgrl_observe.argtypes = [p, p, p]
+    L.pcgrl_get_state.argtypes = [p, p, p, p, p, p, p]
+    L.pcgrl_set_state.argtypes = [p, p, p, p, p, p]
+    L.pcgrl_set_targets.argtypes = [p, p, p]
+    L.pcgrl_obs_shape.argtypes = [p, C.POINTER(i32 * 4)]
+    L.pcgrl_num_metrics.argtypes = [p]
+    L.pcgrl_num_tiles.argtypes = [p]
+    L.pcgrl_bad_action_count.argtypes = [p, C.POINTER(u64), p]
+    L.pcgrl_selftest.argtypes = [C.c_int, C.POINTER(i32)]
+    L.pcgrl_strerror.argtypes = [C.c_int]
+    L.pcgrl_strerror.restype = C.c_char_p
+    _lib = L
+    return L
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise PcgrlError(f"{what} failed: {load().pcgrl_strerror(rc).decode()} ({rc})")
+
+
+def make_config(d: dict) -> PcgrlConfig:
+    c = PcgrlConfig()
+    for k, v in d.items():
+        if k in ("init_cdf", "weights", "target_lo", "target_hi"):
+            arr = getattr(c, k)
+            for i, x in enumerate(v):
+                arr[i] = x
+        else:
+            setattr(c, k, int(v))
+    return c
+
+
+def pcgrl_config_default(problem: int) -> PcgrlConfig:
+    c = PcgrlConfig()
+    _check(load().pcgrl_config_default(problem, C.byref(c)), "pcgrl_config_default")
+    return c
+
+
+def pcgrl_selftest(device: int = 0) -> int:
+    n = C.c_int32(-1)
+    _check(load().pcgrl_selftest(device, C.byref(n)), "pcgrl_selftest")
+    return n.value
+
+
+def _stream_ptr(device) -> int:
+    return torch.cuda.current_stream(device).cuda_stream
+
+
+class Pcgrl:
+    """A batch of GPU-resident environments (one pcgrl_ctx).  Methods carry the C names."""
+
+    def __init__(self, cfg: dict | PcgrlConfig, device: int = 0):
+        self.L = load()
+        self.cfg = cfg if isinstance(cfg, PcgrlConfig) else make_config(cfg)
+        self.device = torch.device("cuda", device)
+        self.h = C.c_void_p()
+        _check(self.L.pcgrl_create(C.byref(self.h), C.byref(self.cfg), device), "pcgrl_create")
+        shp = (C.c_int32 * 4)()
+        _check(self.L.pcgrl_obs_shape(self.h, C.byref(shp)), "pcgrl_obs_shape")
+        self.obs_shape = tuple(shp)
+        self.B = self.cfg.batch
+        self.M = self.L.pcgrl_num_metrics(self.h)
+        self.K = self.L.pcgrl_num_tiles(self.h)
+        self.Hm, self.Wm = self.cfg.max_h, self.cfg.max_w
+
+    def close(self):
+        if getattr(self, "h", None) is not None and self.h:
+            _check(self.L.pcgrl_destroy(self.h), "pcgrl_destroy")
+            self.h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- helpers
+    def _dev(self, t, dtype, shape, name, optional=False):
+        if t is None:
+            if optional:
+                return None
+            raise PcgrlError(f"{name} is required")
+        if not (isinstance(t, torch.Tensor) and t.is_cuda and t.device == self.device):
+            raise PcgrlError(f"{name} must be a tensor on {self.device}")
+        if t.dtype != dtype or tuple(t.shape) != tuple(shape) or not t.is_contiguous():
+            raise PcgrlError(f"{name} must be contiguous {dtype} of shape {tuple(shape)}, "
+                             f"got {t.dtype} {tuple(t.shape)}")
+        return C.c_void_p(t.data_ptr())
+
+    def new_obs(self):
+        return torch.empty(self.obs_shape, dtype=torch.uint8, device=self.device)
+
+    def _st(self):
+        return C.c_void_p(_stream_ptr(self.device))
+
+    # -- the C entry points
+    def pcgrl_reset(self, seed: int, obs=None):
+        o = self._dev(obs, torch.uint8, self.obs_shape, "obs", optional=True)
+        _check(self.L.pcgrl_reset(self.h, C.c_uint64(seed), o, self._st()), "pcgrl_reset")
+
+    def pcgrl_step(self, actions, obs=None, reward=None, done=None):
+        a = self._dev(actions, torch.int32, (self.B,), "actions")
+        o = self._dev(obs, torch.uint8, self.obs_shape, "obs", optional=True)
+        r = self._dev(reward, torch.float32, (self.B,), "reward", optional=True)
+        d = self._dev(done, torch.uint8, (self.B,), "done", optional=True)
+        _check(self.L.pcgrl_step(self.h, a, o, r, d, self._st()), "pcgrl_step")
+
+    def pcgrl_metrics(self, out=None):
+        if out is None:
+            out = torch.empty((self.B, self.M), dtype=torch.int32, device=self.device)
+        o = self._dev(out, torch.int32, (self.B, self.M), "out")
+        _check(self.L.pcgrl_metrics(self.h, o, self._st()), "pcgrl_metrics")
+        return out
+
+    def pcgrl_observe(self, obs=None):
+        if obs is None:
+            obs = self.new_obs()
+        o = self._dev(obs, torch.uint8, self.obs_shape, "obs")
+        _check(self.L.pcgrl_observe(self.h, o, self._st()), "pcgrl_observe")
+        return obs
+
+    def pcgrl_get_state(self):
+        dev = self.device
+        tiles = torch.empty((self.B, self.Hm, self.Wm), dtype=torch.int8, device=dev)
+        frozen = torch.empty((self.B, self.Hm, self.Wm), dtype=torch.uint8, device=dev)
+        hw = torch.empty((self.B, 2), dtype=torch.int16, device=dev)
+        pos = torch.empty((self.B, 2), dtype=torch.int16, device=dev)
+        ctr = torch.empty((self.B, 3), dtype=torch.int32, device=dev)
+        _check(self.L.pcgrl_get_state(self.h, C.c_void_p(tiles.data_ptr()), C.c_void_p(frozen.data_ptr()),
+                                      C.c_void_p(hw.data_ptr()), C.c_void_p(pos.data_ptr()),
+                                      C.c_void_p(ctr.data_ptr()), self._st()), "pcgrl_get_state")
+        return dict(tiles=tiles, frozen=frozen, hw=hw, pos=pos, counters=ctr)
+
+    def pcgrl_set_state(self, tiles, frozen, hw, pos):
+        t = self._dev(tiles, torch.int8, (self.B, self.Hm, self.Wm), "tiles")
+        f = self._dev(frozen, torch.uint8, (self.B, self.Hm, self.Wm), "frozen", optional=True)
+        s = self._dev(hw, torch.int16, (self.B, 2), "hw")
+        q = self._dev(pos, torch.int16, (self.B, 2), "pos")
+        _check(self.L.pcgrl_set_state(self.h, t, f, s, q, self._st()), "pcgrl_set_state")
+
+    def pcgrl_set_targets(self, targets):
+        t = self._dev(targets, torch.int32, (self.B, self.M, 2), "targets")
+        _check(self.L.pcgrl_set_targets(self.h, t, self._st()), "pcgrl_set_targets")
+
+    def pcgrl_bad_action_count(self) -> int:
+        n = C.c_uint64(0)
+        _check(self.L.pcgrl_bad_action_count(self.h, C.byref(n), self._st()), "pcgrl_bad_action_count")
+        return n.value

@@ -1,0 +1,381 @@
+// Host side of the C ABI declared in include/pcgrl.h: argument checks, device state, launches.
+#include "../../include/pcgrl.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <new>
+
+#include "pcgrl_kernels.hip.h"
+
+using namespace pcgrl;
+
+struct pcgrl_ctx {
+  pcgrl_config cfg;
+  int device;
+  int S, G, P, K, M, C;
+  int B_pad, nwaves;
+  size_t word_bytes;
+  size_t lds_bytes;
+  KArgs base;  // device pointers and configuration, copied into every launch
+  void* d_planes;
+  void* d_frozen;
+  void* d_env;
+  void* d_metrics;
+  void* d_targets;
+  void* d_bad;
+};
+
+namespace {
+
+struct DeviceGuard {
+  int prev = -1;
+  bool ok = true;
+  explicit DeviceGuard(int dev) {
+    if (hipGetDevice(&prev) != hipSuccess) prev = -1;
+    ok = hipSetDevice(dev) == hipSuccess;
+  }
+  ~DeviceGuard() {
+    if (prev >= 0) (void)hipSetDevice(prev);
+  }
+};
+
+int tiles_of(int problem) { return problem == PCGRL_BINARY ? 2 : problem == PCGRL_MAZE ? 4 : problem == PCGRL_DUNGEON ? 7 : 0; }
+int planes_of(int problem) { return problem == PCGRL_BINARY ? 1 : problem == PCGRL_MAZE ? 2 : 3; }
+int metrics_of(int problem) { return (problem == PCGRL_DUNGEON ? 3 : 2) + tiles_of(problem); }
+
+int check_config(const pcgrl_config* c) {
+  if (tiles_of(c->problem) == 0) return PCGRL_E_CONFIG;
+  if (c->batch < 1 || c->batch > (1 << 24)) return PCGRL_E_CONFIG;
+  if (c->max_h < 1 || c->max_h > 64 || c->max_w < 1 || c->max_w > 64) return PCGRL_E_CONFIG;
+  if (c->min_h < 1 || c->min_h > c->max_h || c->min_w < 1 || c->min_w > c->max_w) return PCGRL_E_CONFIG;
+  if (c->obs_w < 1 || c->obs_w > 63) return PCGRL_E_CONFIG;
+  if (c->pad_mode != PCGRL_PAD_BORDER && c->pad_mode != PCGRL_PAD_WALL) return PCGRL_E_CONFIG;
+  if (c->pos_mode != PCGRL_POS_SCAN && c->pos_mode != PCGRL_POS_RANDOM) return PCGRL_E_CONFIG;
+  if (c->n_frozen < 0 || c->n_frozen > 8 || c->n_frozen > c->min_h * c->min_w) return PCGRL_E_CONFIG;
+  if (c->max_steps < 1 || c->max_changes < 0) return PCGRL_E_CONFIG;
+  if (c->regions_mode != PCGRL_REGIONS_INCREMENTAL && c->regions_mode != PCGRL_REGIONS_RECOUNT) return PCGRL_E_CONFIG;
+  for (int k = 1; k < tiles_of(c->problem) - 1; ++k)
+    if (c->init_cdf[k] < c->init_cdf[k - 1]) return PCGRL_E_CONFIG;
+  return PCGRL_OK;
+}
+
+template <template <int, int> class Launcher, typename... A>
+int dispatch(int S, int problem, A&&... args) {
+#define PCGRL_CASE(SS, PP) \
+  if (S == SS && problem == PP) return Launcher<SS, PP>::run(static_cast<A&&>(args)...);
+  PCGRL_CASE(16, kBinary) PCGRL_CASE(16, kMaze) PCGRL_CASE(16, kDungeon)
+  PCGRL_CASE(32, kBinary) PCGRL_CASE(32, kMaze) PCGRL_CASE(32, kDungeon)
+  PCGRL_CASE(64, kBinary) PCGRL_CASE(64, kMaze) PCGRL_CASE(64, kDungeon)
+#undef PCGRL_CASE
+  return PCGRL_E_CONFIG;
+}
+
+template <int S, int PROBLEM> struct LaunchStep {
+  static int run(const pcgrl_ctx* ctx, const KArgs& a, hipStream_t st) {
+    hipLaunchKernelGGL((step_kernel<S, PROBLEM>), dim3(ctx->nwaves), dim3(64), ctx->lds_bytes, st, a);
+    return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
+  }
+};
+template <int S, int PROBLEM> struct LaunchInit {
+  static int run(const pcgrl_ctx* ctx, const KArgs& a, hipStream_t st) {
+    hipLaunchKernelGGL((init_kernel<S, PROBLEM>), dim3(ctx->nwaves), dim3(64), ctx->lds_bytes, st, a);
+    return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
+  }
+};
+
+int launch_init(pcgrl_ctx* ctx, int flags, uint64_t seed, uint8_t* obs, hipStream_t st) {
+  KArgs a = ctx->base;
+  a.flags = flags;
+  a.seed = seed;
+  a.obs = obs;
+  return dispatch<LaunchInit>(ctx->S, ctx->cfg.problem, ctx, a, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* pcgrl_strerror(int code) {
+  switch (code) {
+    case PCGRL_OK: return "ok";
+    case PCGRL_E_NULL: return "a required pointer is NULL";
+    case PCGRL_E_CONFIG: return "configuration field out of range";
+    case PCGRL_E_HIP: return "HIP runtime call failed";
+    case PCGRL_E_NOMEM: return "device allocation failed";
+    case PCGRL_E_DEVICE: return "no such device, or not a gfx950 device";
+    default: return "unknown error code";
+  }
+}
+
+int pcgrl_config_default(int32_t problem, pcgrl_config* cfg) {
+  if (!cfg) return PCGRL_E_NULL;
+  const int K = tiles_of(problem);
+  if (K == 0) return PCGRL_E_CONFIG;
+  std::memset(cfg, 0, sizeof(*cfg));
+  cfg->problem = problem;
+  cfg->batch = 1;
+  cfg->max_h = cfg->max_w = cfg->min_h = cfg->min_w = 16;
+  cfg->obs_w = 31;
+  cfg->pad_mode = PCGRL_PAD_BORDER;
+  cfg->pos_mode = PCGRL_POS_SCAN;
+  cfg->max_steps = 1000;
+  cfg->autoreset = 1;
+  cfg->regions_mode = PCGRL_REGIONS_INCREMENTAL;
+  for (int k = 0; k < K; ++k)
+    cfg->init_cdf[k] = k == K - 1 ? 0xFFFFFFFFu : (uint32_t)(((uint64_t)(k + 1) << 32) / (uint64_t)K);
+  const int BIG = 64 * 64;  // no path is this long: "as long as possible"
+  const int base = problem == PCGRL_DUNGEON ? 3 : 2;
+  const int M = metrics_of(problem);
+  for (int i = 0; i < M; ++i) {
+    cfg->target_lo[i] = 0;
+    cfg->target_hi[i] = BIG;
+  }
+  cfg->weights[0] = 5.0f;  // regions: exactly one
+  cfg->target_lo[0] = cfg->target_hi[0] = 1;
+  cfg->weights[1] = 2.0f;  // path / diameter: maximise
+  cfg->target_lo[1] = cfg->target_hi[1] = BIG;
+  if (problem == PCGRL_MAZE) {
+    for (int t = 2; t <= 3; ++t) {  // one player, one door
+      cfg->weights[base + t] = 3.0f;
+      cfg->target_lo[base + t] = cfg->target_hi[base + t] = 1;
+    }
+  } else if (problem == PCGRL_DUNGEON) {
+    cfg->weights[2] = 2.0f;  // nearest enemy at least 4 away
+    cfg->target_lo[2] = 4;
+    cfg->target_hi[2] = BIG;
+    for (int t = 2; t <= 4; ++t) {  // one player, key, door
+      cfg->weights[base + t] = 3.0f;
+      cfg->target_lo[base + t] = cfg->target_hi[base + t] = 1;
+    }
+    cfg->weights[base + 5] = 3.0f;  // two to five enemies
+    cfg->target_lo[base + 5] = 2;
+    cfg->target_hi[base + 5] = 5;
+  }
+  return PCGRL_OK;
+}
+
+int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
+  if (!out || !cfg) return PCGRL_E_NULL;
+  *out = nullptr;
+  int rc = check_config(cfg);
+  if (rc != PCGRL_OK) return rc;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) return PCGRL_E_DEVICE;
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, device) != hipSuccess) return PCGRL_E_DEVICE;
+  if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return PCGRL_E_DEVICE;
+  DeviceGuard guard(device);
+  if (!guard.ok) return PCGRL_E_DEVICE;
+
+  pcgrl_ctx* ctx = new (std::nothrow) pcgrl_ctx();
+  if (!ctx) return PCGRL_E_NOMEM;
+  ctx->cfg = *cfg;
+  ctx->device = device;
+  const int side = cfg->max_h > cfg->max_w ? cfg->max_h : cfg->max_w;
+  ctx->S = side <= 16 ? 16 : side <= 32 ? 32 : 64;
+  ctx->G = 64 / ctx->S;
+  ctx->K = tiles_of(cfg->problem);
+  ctx->P = planes_of(cfg->problem);
+  ctx->M = metrics_of(cfg->problem);
+  ctx->C = ctx->K + (cfg->pad_mode == PCGRL_PAD_BORDER ? 1 : 0);
+  ctx->nwaves = (cfg->batch + ctx->G - 1) / ctx->G;
+  ctx->B_pad = ctx->nwaves * ctx->G;
+  ctx->word_bytes = ctx->S == 64 ? 8 : 4;
+  const size_t E = (size_t)ctx->C * cfg->obs_w * cfg->obs_w;
+  ctx->lds_bytes = ((15 + (size_t)ctx->G * E + 31) / 32 + 2) * 4;
+  if (ctx->lds_bytes > 64 * 1024) {
+    delete ctx;
+    return PCGRL_E_CONFIG;
+  }
+
+  const size_t rows = (size_t)ctx->B_pad * ctx->S;
+  struct { void** p; size_t n; } allocs[] = {
+      {&ctx->d_planes, rows * ctx->word_bytes * ctx->P},
+      {&ctx->d_frozen, rows * ctx->word_bytes},
+      {&ctx->d_env, (size_t)ctx->B_pad * sizeof(EnvRec)},
+      {&ctx->d_metrics, (size_t)ctx->B_pad * kMaxMetrics * sizeof(int32_t)},
+      {&ctx->d_targets, (size_t)ctx->B_pad * kMaxMetrics * 2 * sizeof(int32_t)},
+      {&ctx->d_bad, sizeof(unsigned long long)},
+  };
+  for (auto& al : allocs) *al.p = nullptr;
+  for (auto& al : allocs) {
+    if (hipMalloc(al.p, al.n) != hipSuccess || hipMemset(*al.p, 0, al.n) != hipSuccess) {
+      for (auto& f : allocs)
+        if (*f.p) (void)hipFree(*f.p);
+      delete ctx;
+      return PCGRL_E_NOMEM;
+    }
+  }
+
+  KArgs& a = ctx->base;
+  std::memset(&a, 0, sizeof(a));
+  a.planes = ctx->d_planes;
+  a.frozen = ctx->d_frozen;
+  a.env = static_cast<EnvRec*>(ctx->d_env);
+  a.metrics = static_cast<int32_t*>(ctx->d_metrics);
+  a.targets = static_cast<int32_t*>(ctx->d_targets);
+  a.bad_actions = static_cast<unsigned long long*>(ctx->d_bad);
+  a.B = cfg->batch;
+  a.plane_stride = (int32_t)rows;
+  a.max_h = cfg->max_h;
+  a.max_w = cfg->max_w;
+  a.min_h = cfg->min_h;
+  a.min_w = cfg->min_w;
+  a.obs_w = cfg->obs_w;
+  a.pad_mode = cfg->pad_mode;
+  a.pos_mode = cfg->pos_mode;
+  a.n_frozen = cfg->n_frozen;
+  a.max_steps = cfg->max_steps;
+  a.max_changes = cfg->max_changes;
+  a.autoreset = cfg->autoreset;
+  a.regions_mode = cfg->regions_mode;
+  a.env_obs_bytes = (int32_t)E;
+  for (int k = 0; k < 8; ++k) a.cdf[k] = cfg->init_cdf[k];
+  for (int i = 0; i < kMaxMetrics; ++i) {
+    a.weights[i] = cfg->weights[i];
+    a.target_lo[i] = cfg->target_lo[i];
+    a.target_hi[i] = cfg->target_hi[i];
+  }
+
+  rc = launch_init(ctx, kInitGenerate | kInitMetrics | kInitTargets, 0, nullptr, nullptr);
+  if (rc == PCGRL_OK && hipDeviceSynchronize() != hipSuccess) rc = PCGRL_E_HIP;
+  if (rc != PCGRL_OK) {
+    pcgrl_destroy(ctx);
+    return rc;
+  }
+  *out = ctx;
+  return PCGRL_OK;
+}
+
+int pcgrl_destroy(pcgrl_ctx* ctx) {
+  if (!ctx) return PCGRL_OK;
+  DeviceGuard guard(ctx->device);
+  int rc = hipDeviceSynchronize() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
+  void* bufs[] = {ctx->d_planes, ctx->d_frozen, ctx->d_env, ctx->d_metrics, ctx->d_targets, ctx->d_bad};
+  for (void* b : bufs)
+    if (b && hipFree(b) != hipSuccess) rc = PCGRL_E_HIP;
+  delete ctx;
+  return rc;
+}
+
+int pcgrl_reset(pcgrl_ctx* ctx, uint64_t seed, uint8_t* obs, void* stream) {
+  if (!ctx) return PCGRL_E_NULL;
+  DeviceGuard guard(ctx->device);
+  ctx->base.seed = seed;
+  return launch_init(ctx, kInitGenerate | kInitMetrics | kInitTargets | kInitObs, seed, obs,
+                     static_cast<hipStream_t>(stream));
+}
+
+int pcgrl_step(pcgrl_ctx* ctx, const int32_t* actions, uint8_t* obs, float* reward, uint8_t* done,
+               void* stream) {
+  if (!ctx || !actions) return PCGRL_E_NULL;
+  DeviceGuard guard(ctx->device);
+  KArgs a = ctx->base;
+  a.actions = actions;
+  a.obs = obs;
+  a.reward = reward;
+  a.done = done;
+  return dispatch<LaunchStep>(ctx->S, ctx->cfg.problem, ctx, a, static_cast<hipStream_t>(stream));
+}
+
+int pcgrl_metrics(pcgrl_ctx* ctx, int32_t* out, void* stream) {
+  if (!ctx || !out) return PCGRL_E_NULL;
+  DeviceGuard guard(ctx->device);
+  const int n = ctx->cfg.batch * ctx->M;
+  hipLaunchKernelGGL(copy_metrics_kernel, dim3((n + 255) / 256), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const int32_t*>(ctx->d_metrics),
+                     out, ctx->cfg.batch, ctx->M);
+  return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
+}
+
+int pcgrl_observe(pcgrl_ctx* ctx, uint8_t* obs, void* stream) {
+  if (!ctx || !obs) return PCGRL_E_NULL;
+  DeviceGuard guard(ctx->device);
+  return launch_init(ctx, kInitObs, ctx->base.seed, obs, static_cast<hipStream_t>(stream));
+}
+
+int pcgrl_get_state(pcgrl_ctx* ctx, int8_t* tiles, uint8_t* frozen, int16_t* hw, int16_t* pos,
+                    int32_t* counters, void* stream) {
+  if (!ctx) return PCGRL_E_NULL;
+  DeviceGuard guard(ctx->device);
+  const int n = ctx->cfg.batch * ctx->S;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (ctx->S == 64)
+    hipLaunchKernelGGL(get_state_kernel<uint64_t>, dim3((n + 255) / 256), dim3(256), 0, st, ctx->base,
+                       ctx->S, ctx->P, tiles, frozen, hw, pos, counters);
+  else
+    hipLaunchKernelGGL(get_state_kernel<uint32_t>, dim3((n + 255) / 256), dim3(256), 0, st, ctx->base,
+                       ctx->S, ctx->P, tiles, frozen, hw, pos, counters);
+  return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
+}
+
+int pcgrl_set_state(pcgrl_ctx* ctx, const int8_t* tiles, const uint8_t* frozen, const int16_t* hw,
+                    const int16_t* pos, void* stream) {
+  if (!ctx || !tiles || !hw || !pos) return PCGRL_E_NULL;
+  DeviceGuard guard(ctx->device);
+  const int n = ctx->cfg.batch * ctx->S;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (ctx->S == 64)
+    hipLaunchKernelGGL(set_state_kernel<uint64_t>, dim3((n + 255) / 256), dim3(256), 0, st, ctx->base,
+                       ctx->S, ctx->P, ctx->K, tiles, frozen, hw, pos);
+  else
+    hipLaunchKernelGGL(set_state_kernel<uint32_t>, dim3((n + 255) / 256), dim3(256), 0, st, ctx->base,
+                       ctx->S, ctx->P, ctx->K, tiles, frozen, hw, pos);
+  if (hipGetLastError() != hipSuccess) return PCGRL_E_HIP;
+  return launch_init(ctx, kInitMetrics, ctx->base.seed, nullptr, st);
+}
+
+int pcgrl_set_targets(pcgrl_ctx* ctx, const int32_t* targets, void* stream) {
+  if (!ctx || !targets) return PCGRL_E_NULL;
+  DeviceGuard guard(ctx->device);
+  const int n = ctx->cfg.batch * ctx->M * 2;
+  hipLaunchKernelGGL(set_targets_kernel, dim3((n + 255) / 256), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), targets, static_cast<int32_t*>(ctx->d_targets),
+                     ctx->cfg.batch, ctx->M);
+  return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
+}
+
+int pcgrl_obs_shape(const pcgrl_ctx* ctx, int32_t out[4]) {
+  if (!ctx || !out) return PCGRL_E_NULL;
+  out[0] = ctx->cfg.batch;
+  out[1] = ctx->C;
+  out[2] = ctx->cfg.obs_w;
+  out[3] = ctx->cfg.obs_w;
+  return PCGRL_OK;
+}
+
+int pcgrl_num_metrics(const pcgrl_ctx* ctx) { return ctx ? ctx->M : PCGRL_E_NULL; }
+int pcgrl_num_tiles(const pcgrl_ctx* ctx) { return ctx ? ctx->K : PCGRL_E_NULL; }
+
+int pcgrl_bad_action_count(pcgrl_ctx* ctx, uint64_t* out, void* stream) {
+  if (!ctx || !out) return PCGRL_E_NULL;
+  DeviceGuard guard(ctx->device);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  unsigned long long v = 0;
+  if (hipMemcpyAsync(&v, ctx->d_bad, sizeof(v), hipMemcpyDeviceToHost, st) != hipSuccess) return PCGRL_E_HIP;
+  if (hipStreamSynchronize(st) != hipSuccess) return PCGRL_E_HIP;
+  *out = v;
+  return PCGRL_OK;
+}
+
+int pcgrl_selftest(int device, int32_t* mismatches) {
+  if (!mismatches) return PCGRL_E_NULL;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) return PCGRL_E_DEVICE;
+  DeviceGuard guard(device);
+  int32_t* d = nullptr;
+  if (hipMalloc(reinterpret_cast<void**>(&d), sizeof(int32_t)) != hipSuccess) return PCGRL_E_NOMEM;
+  int rc = PCGRL_OK;
+  if (hipMemset(d, 0, sizeof(int32_t)) != hipSuccess) rc = PCGRL_E_HIP;
+  if (rc == PCGRL_OK) {
+    hipLaunchKernelGGL(selftest_kernel, dim3(1), dim3(64), 0, nullptr, d);
+    if (hipGetLastError() != hipSuccess) rc = PCGRL_E_HIP;
+  }
+  if (rc == PCGRL_OK && hipMemcpy(mismatches, d, sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess)
+    rc = PCGRL_E_HIP;
+  (void)hipFree(d);
+  return rc;
+}
+
+}  // extern "C"

@@ -1,0 +1,912 @@
+// Device code of the batched PCGRL step for gfx950 (wave64).
+//
+// Layout.  A level lives in registers as row bitboards: lane (g, y) of a wavefront holds row y of
+// the level in group g, one word per tile-code bit-plane (bit x = column x).  S = 16, 32 or 64 is
+// the padded side; a wavefront therefore carries G = 64 / S levels.  Vertical neighbours are
+// reached with DPP lane shifts, horizontal ones with word shifts, so one breadth-first layer of a
+// whole level is a handful of full-rate vector instructions and no memory traffic.  LDS is used
+// only to stage the observation as a packed bit stream before it is widened to bytes.
+//
+// Everything a group shares (shape, position, metrics, ...) is held redundantly in every lane of
+// the group; "uniform" below means uniform inside one group.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pcgrl {
+
+constexpr int kMaxMetrics = 16;
+
+enum : int { kBinary = 0, kMaze = 1, kDungeon = 2 };
+enum : int { kPadBorder = 0, kPadWall = 1 };
+enum : int { kPosScan = 0, kPosRandom = 1 };
+enum : int { kRegionsIncremental = 0, kRegionsRecount = 1 };
+enum : int { kInitGenerate = 1, kInitMetrics = 2, kInitObs = 4, kInitTargets = 8 };
+
+// Per-environment scalars, 32 bytes, read and written as two 16-byte words.
+struct __attribute__((aligned(16))) EnvRec {
+  uint8_t h, w, py, px;
+  int32_t t;
+  int32_t n_changes;
+  int32_t episode;
+  uint64_t key;  // generator key of (seed, env, episode)
+  uint64_t pad_;
+};
+static_assert(sizeof(EnvRec) == 32, "EnvRec must be 32 bytes");
+
+struct KArgs {
+  void* planes;      // word [P][plane_stride], index env * S + y
+  void* frozen;      // word [plane_stride]
+  EnvRec* env;       // [B_pad]
+  int32_t* metrics;  // [B_pad][16]
+  int32_t* targets;  // [B_pad][16][2]
+  const int32_t* actions;
+  uint8_t* obs;
+  float* reward;
+  uint8_t* done;
+  unsigned long long* bad_actions;
+  uint64_t seed;
+  int32_t B, plane_stride;
+  int32_t max_h, max_w, min_h, min_w;
+  int32_t obs_w, pad_mode, pos_mode, n_frozen, max_steps, max_changes, autoreset, regions_mode;
+  int32_t env_obs_bytes;  // C * obs_w * obs_w
+  int32_t flags;          // init kernel only
+  uint32_t cdf[8];
+  float weights[kMaxMetrics];
+  int32_t target_lo[kMaxMetrics], target_hi[kMaxMetrics];
+};
+
+template <int S> struct RowWord { using T = uint32_t; };
+template <> struct RowWord<64> { using T = uint64_t; };
+
+template <int PROBLEM> struct Prob;
+template <> struct Prob<kBinary> { static constexpr int K = 2, P = 1, M = 4, CNT = 2; };
+template <> struct Prob<kMaze> { static constexpr int K = 4, P = 2, M = 6, CNT = 2; };
+template <> struct Prob<kDungeon> { static constexpr int K = 7, P = 3, M = 10, CNT = 3; };
+
+// --------------------------------------------------------------- generator
+// Counter-based numbers: the mixing function of the published splitmix64 generator applied to
+// key + golden * (stream, counter).  Integer only, so CPU and GPU agree bit for bit.
+
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+constexpr uint64_t kGolden = 0x9E3779B97F4A7C15ull;
+__device__ __forceinline__ uint64_t env_key(uint64_t seed, uint64_t env, uint64_t episode) {
+  uint64_t k0 = mix64(seed + kGolden * (env + 1));
+  return mix64(k0 ^ (0xD1B54A32D192ED03ull * (episode + 1)));
+}
+__device__ __forceinline__ uint64_t draw(uint64_t key, uint32_t stream, uint32_t counter) {
+  uint64_t c = ((uint64_t)stream << 32) + (uint64_t)counter + 1;
+  return mix64(key + kGolden * c);
+}
+__device__ __forceinline__ int below(uint32_t r, int n) { return (int)__umulhi(r, (uint32_t)n); }
+
+// ------------------------------------------------------------ lane algebra
+
+template <int CTRL> __device__ __forceinline__ uint32_t dpp_zero_fill(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
+}
+constexpr int kRowShr1 = 0x111, kRowShl1 = 0x101, kWaveShr1 = 0x138, kWaveShl1 = 0x130;
+
+template <int S> struct Lanes {
+  using W = typename RowWord<S>::T;
+  static constexpr int G = 64 / S;
+  int lane, g, y, gbase;
+  __device__ __forceinline__ Lanes() {
+    lane = (int)(threadIdx.x & 63u);
+    g = lane / S;
+    y = lane % S;
+    gbase = g * S;
+  }
+  // value held by the lane of row y-1 of the same level (0 for the top row)
+  __device__ __forceinline__ W from_above(W v) const {
+    if constexpr (S == 16) {
+      return dpp_zero_fill<kRowShr1>(v);
+    } else if constexpr (S == 32) {
+      uint32_t r = dpp_zero_fill<kWaveShr1>(v);
+      return y == 0 ? 0u : r;
+    } else {
+      uint32_t lo = dpp_zero_fill<kWaveShr1>((uint32_t)v);
+      uint32_t hi = dpp_zero_fill<kWaveShr1>((uint32_t)(v >> 32));
+      return ((uint64_t)hi << 32) | lo;
+    }
+  }
+  // value held by the lane of row y+1 (0 for the bottom row)
+  __device__ __forceinline__ W from_below(W v) const {
+    if constexpr (S == 16) {
+      return dpp_zero_fill<kRowShl1>(v);
+    } else if constexpr (S == 32) {
+      uint32_t r = dpp_zero_fill<kWaveShl1>(v);
+      return y == S - 1 ? 0u : r;
+    } else {
+      uint32_t lo = dpp_zero_fill<kWaveShl1>((uint32_t)v);
+      uint32_t hi = dpp_zero_fill<kWaveShl1>((uint32_t)(v >> 32));
+      return ((uint64_t)hi << 32) | lo;
+    }
+  }
+  // the four-neighbour dilation of a cell set (the set itself included), not yet masked
+  __device__ __forceinline__ W dilate(W f) const {
+    return f | (W)(f << 1) | (W)(f >> 1) | from_above(f) | from_below(f);
+  }
+  // bits of a wave ballot that belong to this lane's group, moved down to bit 0
+  __device__ __forceinline__ uint64_t gbits(uint64_t ballot) const {
+    if constexpr (S == 64) return ballot;
+    return (ballot >> gbase) & ((1ull << S) - 1ull);
+  }
+  __device__ __forceinline__ bool gany(bool pred) const {
+    return gbits(__builtin_amdgcn_ballot_w64(pred)) != 0;
+  }
+  __device__ __forceinline__ int gsum(int v) const {
+#pragma unroll
+    for (int o = S / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+  }
+  __device__ __forceinline__ int gmax(int v) const {
+#pragma unroll
+    for (int o = S / 2; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o));
+    return v;
+  }
+  // value of lane `row` of this group
+  __device__ __forceinline__ W gread(W v, int row) const { return (W)__shfl(v, gbase + row); }
+  __device__ __forceinline__ int gread_i(int v, int row) const { return __shfl(v, gbase + row); }
+};
+
+__device__ __forceinline__ int popc(uint32_t v) { return __popc(v); }
+__device__ __forceinline__ int popc(uint64_t v) { return __popcll(v); }
+__device__ __forceinline__ int ctz(uint32_t v) { return __ffs(v) - 1; }
+__device__ __forceinline__ int ctz(uint64_t v) { return __ffsll((unsigned long long)v) - 1; }
+
+template <int S> __device__ __forceinline__ bool wave_any(bool pred) {
+  return __builtin_amdgcn_ballot_w64(pred) != 0;
+}
+
+// The cell with the lowest row-major index of a set, as a one-cell set (empty if the set is).
+template <int S>
+__device__ __forceinline__ typename RowWord<S>::T first_cell(const Lanes<S>& L,
+                                                             typename RowWord<S>::T set) {
+  using W = typename RowWord<S>::T;
+  uint64_t rows = L.gbits(__builtin_amdgcn_ballot_w64(set != 0));
+  int first_row = rows ? ctz(rows) : -1;
+  return L.y == first_row ? (W)(set & (~set + 1)) : (W)0;
+}
+
+// ---------------------------------------------------------------- tile planes
+
+template <int PROBLEM, typename W>
+__device__ __forceinline__ W channel_row(const W (&p)[Prob<PROBLEM>::P], W inside, int c) {
+  W r = inside;
+#pragma unroll
+  for (int i = 0; i < Prob<PROBLEM>::P; ++i) r &= ((c >> i) & 1) ? p[i] : (W)~p[i];
+  return r;
+}
+
+// ------------------------------------------------------------------ metrics
+
+// One sweep of the two-sweep diameter estimate: breadth-first layers from `seed` inside `pass`.
+// Returns the eccentricity of the seed and leaves in `last` the cells of the last layer
+// (the seed itself when nothing else is reachable).
+template <int S>
+__device__ __forceinline__ int sweep(const Lanes<S>& L, typename RowWord<S>::T seed,
+                                     typename RowWord<S>::T pass, typename RowWord<S>::T& last) {
+  using W = typename RowWord<S>::T;
+  W V = seed, lastN = seed;
+  int it = 0, last_it = 0;
+  for (;;) {
+    ++it;
+    W Vn = L.dilate(V) & pass;
+    W N = Vn ^ V;
+    bool ch = N != 0;
+    if (ch) {
+      lastN = N;
+      last_it = it;
+    }
+    V = Vn;
+    if (!wave_any<S>(ch)) break;
+  }
+  int d = L.gmax(last_it);
+  last = last_it == d ? lastN : (W)0;
+  return d;
+}
+
+// Binary domain, footnote: sweep from the first walkable cell x, then from the far end of the
+// longest shortest path out of x (lowest row-major index among equally far cells).
+template <int S>
+__device__ __forceinline__ int two_sweep_diameter(const Lanes<S>& L, typename RowWord<S>::T pass) {
+  using W = typename RowWord<S>::T;
+  W x = first_cell<S>(L, pass);
+  W far;
+  sweep<S>(L, x, pass, far);
+  W y = first_cell<S>(L, far);
+  W unused;
+  return sweep<S>(L, y, pass, unused);
+}
+
+// Distance from a source set to the nearest cell of a target set, -1 if none is reachable.
+// `reached` receives the target cells found in the layer of the first hit.
+template <int S>
+__device__ __forceinline__ int nearest(const Lanes<S>& L, typename RowWord<S>::T src,
+                                       typename RowWord<S>::T tgt, typename RowWord<S>::T pass,
+                                       typename RowWord<S>::T& reached) {
+  using W = typename RowWord<S>::T;
+  W V = src;
+  int d = -1, it = 0;
+  reached = 0;
+  for (;;) {
+    ++it;
+    W Vn = L.dilate(V) & pass;
+    bool ch = Vn != V;
+    uint64_t hit = L.gbits(__builtin_amdgcn_ballot_w64((Vn & tgt) != 0));
+    V = Vn;
+    if (hit != 0 && d < 0) {
+      d = it;
+      reached = Vn & tgt;
+      V = 0;
+      pass = 0;
+    }
+    if (!wave_any<S>(ch && d < 0)) break;
+  }
+  return d;
+}
+
+// Dungeon: one flood from the players that looks for keys and enemies at the same time.
+template <int S>
+__device__ __forceinline__ void nearest_two(const Lanes<S>& L, typename RowWord<S>::T src,
+                                            typename RowWord<S>::T tgt_a, typename RowWord<S>::T tgt_b,
+                                            typename RowWord<S>::T pass, int& d_a,
+                                            typename RowWord<S>::T& reached_a, int& d_b) {
+  using W = typename RowWord<S>::T;
+  W V = src;
+  int it = 0;
+  d_a = -1;
+  d_b = -1;
+  reached_a = 0;
+  for (;;) {
+    ++it;
+    W Vn = L.dilate(V) & pass;
+    bool ch = Vn != V;
+    uint64_t hit_a = L.gbits(__builtin_amdgcn_ballot_w64((Vn & tgt_a) != 0));
+    uint64_t hit_b = L.gbits(__builtin_amdgcn_ballot_w64((Vn & tgt_b) != 0));
+    V = Vn;
+    if (hit_a != 0 && d_a < 0) {
+      d_a = it;
+      reached_a = Vn & tgt_a;
+    }
+    if (hit_b != 0 && d_b < 0) d_b = it;
+    bool finished = d_a >= 0 && d_b >= 0;
+    if (finished) {
+      V = 0;
+      pass = 0;
+    }
+    if (!wave_any<S>(ch && !finished)) break;
+  }
+}
+
+// Number of 4-connected components of `pass`: single cells without walkable neighbour are counted
+// with a popcount, every other component is flooded once from its lowest cell.
+template <int S>
+__device__ __forceinline__ int regions_full(const Lanes<S>& L, typename RowWord<S>::T pass) {
+  using W = typename RowWord<S>::T;
+  W nb = (W)(pass << 1) | (W)(pass >> 1) | L.from_above(pass) | L.from_below(pass);
+  W iso = pass & ~nb;
+  int count = L.gsum(popc(iso));
+  W R = pass & ~iso;
+  for (;;) {
+    W V = first_cell<S>(L, R);
+    if (!wave_any<S>(V != 0)) break;
+    count += L.gany(V != 0) ? 1 : 0;
+    for (;;) {
+      W Vn = L.dilate(V) & R;
+      bool ch = Vn != V;
+      V = Vn;
+      if (!wave_any<S>(ch)) break;
+    }
+    R &= ~V;
+  }
+  return count;
+}
+
+// Number of distinct components of `passw` (the level with the edited cell walled off) among the
+// walkable four-neighbours `nbr` of that cell.  Floods start from the neighbours one after the
+// other and stop as soon as every remaining neighbour is reached or the flood stalls; the last
+// unreached neighbour needs no flood of its own.
+template <int S>
+__device__ __forceinline__ int neighbour_components(const Lanes<S>& L, typename RowWord<S>::T nbr,
+                                                    typename RowWord<S>::T passw) {
+  using W = typename RowWord<S>::T;
+  W U = nbr;
+  int left = L.gsum(popc(U));
+  int k = 0;
+  for (;;) {
+    bool go = left >= 2;
+    if (!go && left == 1) {
+      k += 1;
+      left = 0;
+      U = 0;
+    }
+    if (!wave_any<S>(go)) break;
+    W V = go ? first_cell<S>(L, U) : (W)0;
+    W pw = go ? passw : (W)0;
+    k += go ? 1 : 0;
+    for (;;) {
+      W Vn = L.dilate(V) & pw;
+      bool ch = Vn != V;
+      V = Vn;
+      bool open = L.gany((U & ~V) != 0);  // some neighbour still unreached
+      if (!open) {                        // everything met: this group is finished for good
+        U = 0;
+        V = 0;
+        pw = 0;
+      }
+      if (!wave_any<S>(ch && open)) break;
+    }
+    U &= ~V;
+    left = L.gsum(popc(U));
+  }
+  return k;
+}
+
+// Full metric vector of the level held by a group (all M entries).
+template <int S, int PROBLEM>
+__device__ __forceinline__ void full_metrics(const Lanes<S>& L,
+                                             const typename RowWord<S>::T (&p)[Prob<PROBLEM>::P],
+                                             typename RowWord<S>::T inside, bool active,
+                                             int (&m)[Prob<PROBLEM>::M]) {
+  using W = typename RowWord<S>::T;
+  using PR = Prob<PROBLEM>;
+  W in = active ? inside : (W)0;
+  W wall = channel_row<PROBLEM, W>(p, in, 1);
+  W pass = in & ~wall;
+#pragma unroll
+  for (int k = 0; k < PR::K; ++k) m[PR::CNT + k] = L.gsum(popc(channel_row<PROBLEM, W>(p, in, k)));
+  m[0] = regions_full<S>(L, pass);
+  if constexpr (PROBLEM == kBinary) {
+    m[1] = two_sweep_diameter<S>(L, pass);
+  } else if constexpr (PROBLEM == kMaze) {
+    W r;
+    int d = nearest<S>(L, channel_row<PROBLEM, W>(p, in, 2), channel_row<PROBLEM, W>(p, in, 3), pass, r);
+    m[1] = d < 0 ? 0 : d;
+  } else {
+    W k1, r;
+    int d1, de;
+    nearest_two<S>(L, channel_row<PROBLEM, W>(p, in, 2), channel_row<PROBLEM, W>(p, in, 3),
+                   channel_row<PROBLEM, W>(p, in, 5), pass, d1, k1, de);
+    int d2 = nearest<S>(L, k1, channel_row<PROBLEM, W>(p, in, 4), pass, r);
+    m[1] = (d1 >= 0 && d2 >= 0) ? d1 + d2 : 0;
+    m[2] = de < 0 ? 0 : de;
+  }
+}
+
+__device__ __forceinline__ int loss(int v, int lo, int hi) { return max(0, max(lo - v, v - hi)); }
+
+// ---------------------------------------------------------------- episodes
+
+// Start of an episode: shape, tiles, pinpoints, first position, all from the env's key.
+template <int S, int PROBLEM>
+__device__ __forceinline__ void begin_episode(const KArgs& a, const Lanes<S>& L, uint64_t key,
+                                              typename RowWord<S>::T (&p)[Prob<PROBLEM>::P],
+                                              typename RowWord<S>::T& fz, int& h, int& w, int& py,
+                                              int& px) {
+  using W = typename RowWord<S>::T;
+  using PR = Prob<PROBLEM>;
+  h = a.max_h;
+  w = a.max_w;
+  if (a.min_h < a.max_h) h = a.min_h + below((uint32_t)(draw(key, 0, 0) >> 32), a.max_h - a.min_h + 1);
+  if (a.min_w < a.max_w) w = a.min_w + below((uint32_t)(draw(key, 0, 1) >> 32), a.max_w - a.min_w + 1);
+  bool empty_start = true;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) empty_start = empty_start && a.cdf[k] == 0;
+#pragma unroll
+  for (int i = 0; i < PR::P; ++i) p[i] = 0;
+  if (!empty_start && L.y < h) {
+    for (int x = 0; x < w; ++x) {
+      uint32_t r = (uint32_t)(draw(key, 1, (uint32_t)(L.y * a.max_w + x)) >> 32);
+      int tile = 0;  // thresholds are non-decreasing: the first one above r = how many are <= r
+#pragma unroll
+      for (int k = 0; k < PR::K - 1; ++k) tile += r >= a.cdf[k] ? 1 : 0;
+#pragma unroll
+      for (int i = 0; i < PR::P; ++i) p[i] |= (W)((tile >> i) & 1) << x;
+    }
+  }
+  fz = 0;
+  int placed = 0;
+  for (uint32_t att = 0; att < 64 && placed < a.n_frozen; ++att) {
+    uint64_t u = draw(key, 2, att);
+    int fy = below((uint32_t)(u >> 32), h), fx = below((uint32_t)u, w);
+    bool mine = L.y == fy;
+    bool fresh = L.gany(mine && ((fz >> fx) & 1) == 0);
+    if (fresh) {
+      if (mine) fz |= (W)1 << fx;
+      ++placed;
+    }
+  }
+  py = 0;
+  px = 0;
+  if (a.pos_mode == kPosRandom) {
+    uint64_t u = draw(key, 3, 0);
+    py = below((uint32_t)(u >> 32), h);
+    px = below((uint32_t)u, w);
+  }
+}
+
+template <typename W> __device__ __forceinline__ W inside_row(int y, int h, int w) {
+  W full = w >= (int)(8 * sizeof(W)) ? (W)~(W)0 : (W)(((W)1 << w) - 1);
+  return y < h ? full : (W)0;
+}
+
+// -------------------------------------------------------------- observation
+
+// Writes the observations of the up to G levels of this wavefront.  The window rows are first
+// packed as a bit stream in LDS (bit j of the stream = byte j of the wave's contiguous output
+// region, shifted so that 16-bit chunks line up with 16-byte aligned addresses), then every lane
+// widens 16 bits to 16 bytes and issues one aligned 16-byte store.
+template <int S, int PROBLEM>
+__device__ __forceinline__ void write_obs(const KArgs& a, const Lanes<S>& L, uint32_t* lds,
+                                          const typename RowWord<S>::T (&p)[Prob<PROBLEM>::P],
+                                          typename RowWord<S>::T inside, int qy, int qx, int env0,
+                                          int nvalid) {
+  using W = typename RowWord<S>::T;
+  using PR = Prob<PROBLEM>;
+  const int ow = a.obs_w, r = ow >> 1;
+  const int C = PR::K + (a.pad_mode == kPadBorder ? 1 : 0);
+  const int E = a.env_obs_bytes;
+  uint8_t* region = a.obs + (size_t)env0 * (size_t)E;
+  const int d = (int)((uintptr_t)region & 15u);
+  const int total = d + nvalid * E;  // stream length in bits
+  const int nwords = (total + 31) >> 5;
+  for (int i = L.lane; i < nwords; i += 64) lds[i] = 0;
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+
+  if (L.g < nvalid) {
+    const uint64_t owmask = (1ull << ow) - 1ull;  // ow <= 63
+    const int y0 = qy - r, x0 = qx - r;
+    const int i_first = (L.y - y0) & (S - 1);
+    // part of the window row that lies outside the map's columns
+    uint64_t in64 = (uint64_t)inside;
+    uint64_t in_win = (x0 >= 0 ? (in64 >> x0) : (in64 << (-x0))) & owmask;
+    for (int i = i_first; i < ow; i += S) {
+      const bool real = (y0 + i) == L.y;
+      for (int c = 0; c < C; ++c) {
+        uint64_t bits;
+        if (real) {
+          if (c < PR::K) {
+            uint64_t row = (uint64_t)channel_row<PROBLEM, W>(p, inside, c);
+            bits = (x0 >= 0 ? (row >> x0) : (row << (-x0))) & owmask;
+            if (a.pad_mode == kPadWall && c == 1) bits |= ~in_win & owmask;
+          } else {
+            bits = ~in_win & owmask;
+          }
+        } else {
+          bool padc = a.pad_mode == kPadBorder ? (c == PR::K) : (c == 1);
+          bits = padc ? owmask : 0ull;
+        }
+        if (bits != 0) {
+          int off = d + L.g * E + (c * ow + i) * ow;
+          int w0 = off >> 5, s = off & 31;
+          uint64_t lo = bits << s;
+          uint32_t hi = s ? (uint32_t)(bits >> (64 - s)) : 0u;
+          if ((uint32_t)lo) atomicOr(&lds[w0], (uint32_t)lo);
+          if ((uint32_t)(lo >> 32)) atomicOr(&lds[w0 + 1], (uint32_t)(lo >> 32));
+          if (hi) atomicOr(&lds[w0 + 2], hi);
+        }
+      }
+    }
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+
+  uint8_t* base = region - d;  // 16-byte aligned
+  const int nchunks = (total + 15) >> 4;
+  const uint16_t* lds16 = reinterpret_cast<const uint16_t*>(lds);
+  for (int q = L.lane; q < nchunks; q += 64) {
+    uint32_t b = lds16[q];
+    uint4 v;
+    v.x = __umul24(b & 15u, 0x00204081u) & 0x01010101u;
+    v.y = __umul24((b >> 4) & 15u, 0x00204081u) & 0x01010101u;
+    v.z = __umul24((b >> 8) & 15u, 0x00204081u) & 0x01010101u;
+    v.w = __umul24((b >> 12) & 15u, 0x00204081u) & 0x01010101u;
+    int lo = q << 4;
+    if (lo >= d && lo + 16 <= total) {
+      *reinterpret_cast<uint4*>(base + lo) = v;
+    } else {
+      uint32_t wds[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int t = 0; t < 16; ++t) {
+        int pos = lo + t;
+        if (pos >= d && pos < total) base[pos] = (uint8_t)((wds[t >> 2] >> ((t & 3) * 8)) & 0xffu);
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------ kernels
+
+template <int S, int PROBLEM>
+__device__ __forceinline__ void load_metrics(const int32_t* src, int (&m)[Prob<PROBLEM>::M]) {
+  constexpr int M = Prob<PROBLEM>::M;
+  const int4* v = reinterpret_cast<const int4*>(src);
+#pragma unroll
+  for (int q = 0; q < (M + 3) / 4; ++q) {
+    int4 t = v[q];
+    if (4 * q + 0 < M) m[4 * q + 0] = t.x;
+    if (4 * q + 1 < M) m[4 * q + 1] = t.y;
+    if (4 * q + 2 < M) m[4 * q + 2] = t.z;
+    if (4 * q + 3 < M) m[4 * q + 3] = t.w;
+  }
+}
+
+template <int S, int PROBLEM>
+__device__ __forceinline__ void store_metrics(int32_t* dst, const int (&m)[Prob<PROBLEM>::M]) {
+  constexpr int M = Prob<PROBLEM>::M;
+  int4* v = reinterpret_cast<int4*>(dst);
+#pragma unroll
+  for (int q = 0; q < (M + 3) / 4; ++q) {
+    int4 t;
+    t.x = 4 * q + 0 < M ? m[4 * q + 0] : 0;
+    t.y = 4 * q + 1 < M ? m[4 * q + 1] : 0;
+    t.z = 4 * q + 2 < M ? m[4 * q + 2] : 0;
+    t.w = 4 * q + 3 < M ? m[4 * q + 3] : 0;
+    v[q] = t;
+  }
+}
+
+// Reset / refresh / observe: flags choose between generating a fresh episode 0 from the seed or
+// loading the stored level, recomputing all metrics, restoring default targets, writing the
+// observation.
+template <int S, int PROBLEM>
+__global__ __launch_bounds__(64) void init_kernel(KArgs a) {
+  using W = typename RowWord<S>::T;
+  using PR = Prob<PROBLEM>;
+  extern __shared__ uint32_t lds[];
+  Lanes<S> L;
+  constexpr int G = 64 / S;
+  const int env0 = (int)blockIdx.x * G;
+  const int env = env0 + L.g;
+  const bool valid = env < a.B;
+  const int nvalid = min(G, a.B - env0);
+  W* planes = reinterpret_cast<W*>(a.planes);
+  W* frozen = reinterpret_cast<W*>(a.frozen);
+  const size_t ridx = (size_t)env * S + L.y;  // inside the padded allocation even when !valid
+
+  W p[PR::P], fz;
+  int h, w, py, px;
+  EnvRec er;
+  if (a.flags & kInitGenerate) {
+    er.key = env_key(a.seed, (uint64_t)env, 0);
+    er.t = 0;
+    er.n_changes = 0;
+    er.episode = 0;
+    er.pad_ = 0;
+    begin_episode<S, PROBLEM>(a, L, er.key, p, fz, h, w, py, px);
+    er.h = (uint8_t)h;
+    er.w = (uint8_t)w;
+    er.py = (uint8_t)py;
+    er.px = (uint8_t)px;
+#pragma unroll
+    for (int i = 0; i < PR::P; ++i) planes[(size_t)i * a.plane_stride + ridx] = p[i];
+    frozen[ridx] = fz;
+    if (L.y == 0) a.env[env] = er;
+  } else {
+    er = a.env[env];
+    h = er.h;
+    w = er.w;
+    py = er.py;
+    px = er.px;
+#pragma unroll
+    for (int i = 0; i < PR::P; ++i) p[i] = planes[(size_t)i * a.plane_stride + ridx];
+  }
+  const W inside = inside_row<W>(L.y, h, w);
+  if (a.flags & kInitMetrics) {
+    int m[PR::M];
+    full_metrics<S, PROBLEM>(L, p, inside, valid, m);
+    if (L.y == 0) store_metrics<S, PROBLEM>(a.metrics + (size_t)env * kMaxMetrics, m);
+  }
+  if ((a.flags & kInitTargets) && L.y < PR::M) {
+    a.targets[((size_t)env * kMaxMetrics + L.y) * 2 + 0] = a.target_lo[L.y];
+    a.targets[((size_t)env * kMaxMetrics + L.y) * 2 + 1] = a.target_hi[L.y];
+  }
+  if ((a.flags & kInitObs) && a.obs != nullptr)
+    write_obs<S, PROBLEM>(a, L, lds, p, inside, py, px, env0, nvalid);
+}
+
+// One environment step of every level (see pcgrl_step in the public header).
+template <int S, int PROBLEM>
+__global__ __launch_bounds__(64) void step_kernel(KArgs a) {
+  using W = typename RowWord<S>::T;
+  using PR = Prob<PROBLEM>;
+  extern __shared__ uint32_t lds[];
+  Lanes<S> L;
+  constexpr int G = 64 / S;
+  const int env0 = (int)blockIdx.x * G;
+  const int env = env0 + L.g;
+  const bool valid = env < a.B;
+  const int nvalid = min(G, a.B - env0);
+  W* planes = reinterpret_cast<W*>(a.planes);
+  W* frozen = reinterpret_cast<W*>(a.frozen);
+  const size_t ridx = (size_t)env * S + L.y;
+
+  // ---- load
+  W p[PR::P];
+#pragma unroll
+  for (int i = 0; i < PR::P; ++i) p[i] = planes[(size_t)i * a.plane_stride + ridx];
+  EnvRec er = a.env[env];
+  int h = er.h, w = er.w, py = er.py, px = er.px;
+  const int act = valid ? a.actions[env] : -1;
+  const W fzrow = frozen[(size_t)env * S + py];
+  int mo[PR::M];
+  load_metrics<S, PROBLEM>(a.metrics + (size_t)env * kMaxMetrics, mo);
+  W inside = inside_row<W>(L.y, h, w);
+
+  // ---- edit (Methods / Training: the agent may change the tile it stands on)
+  int old_code = 0;
+#pragma unroll
+  for (int i = 0; i < PR::P; ++i) old_code |= (int)((L.gread(p[i], py) >> px) & 1) << i;
+  const bool in_range = act >= 0 && act < PR::K;
+  const bool is_frozen = ((fzrow >> px) & 1) != 0;
+  const bool changed = valid && in_range && !is_frozen && act != old_code;
+  if (valid && !in_range && L.y == 0) atomicAdd(a.bad_actions, 1ull);
+  if (changed && L.y == py) {
+#pragma unroll
+    for (int i = 0; i < PR::P; ++i) {
+      p[i] = (p[i] & ~((W)1 << px)) | ((W)((act >> i) & 1) << px);
+      planes[(size_t)i * a.plane_stride + ridx] = p[i];
+    }
+  }
+
+  // ---- metrics, only where the edit modified the map (Methods / Task)
+  int mn[PR::M];
+#pragma unroll
+  for (int i = 0; i < PR::M; ++i) mn[i] = mo[i];
+  float reward = 0.0f;
+  if (wave_any<S>(changed)) {
+    const W in = changed ? inside : (W)0;  // unchanged levels look empty: their loops end at once
+    const W wall = channel_row<PROBLEM, W>(p, in, 1);
+    const W pass = in & ~wall;
+    // tile counts: one cell moved from one tile type to another
+#pragma unroll
+    for (int k = 0; k < PR::K; ++k)
+      mn[PR::CNT + k] += (changed && act == k ? 1 : 0) - (changed && old_code == k ? 1 : 0);
+    const bool was_pass = old_code != 1, now_pass = act != 1;
+    // regions
+    if (a.regions_mode == kRegionsRecount) {
+      int rc = regions_full<S>(L, pass);
+      if (changed) mn[0] = rc;
+    } else {
+      const bool flip = changed && was_pass != now_pass;
+      if (wave_any<S>(flip)) {
+        W cell = (flip && L.y == py) ? (W)1 << px : (W)0;
+        W passw = flip ? (pass & ~cell) : (W)0;
+        W nbr = (L.dilate(cell) & ~cell) & passw;
+        int k = neighbour_components<S>(L, nbr, passw);
+        if (flip) mn[0] = mo[0] + (now_pass ? 1 - k : k - 1);
+      }
+    }
+    // paths
+    if constexpr (PROBLEM == kBinary) {
+      int dm = two_sweep_diameter<S>(L, pass);
+      if (changed) mn[1] = dm;
+    } else if constexpr (PROBLEM == kMaze) {
+      W r;
+      int dd = nearest<S>(L, channel_row<PROBLEM, W>(p, in, 2), channel_row<PROBLEM, W>(p, in, 3), pass, r);
+      if (changed) mn[1] = dd < 0 ? 0 : dd;
+    } else {
+      // swapping empty and chest changes neither the graph nor any source or target set
+      const bool plain = (old_code == 0 || old_code == 6) && (act == 0 || act == 6);
+      const bool need = changed && !plain;
+      if (wave_any<S>(need)) {
+        const W inn = need ? in : (W)0;
+        const W passn = need ? pass : (W)0;
+        W k1, r;
+        int d1, de;
+        nearest_two<S>(L, channel_row<PROBLEM, W>(p, inn, 2), channel_row<PROBLEM, W>(p, inn, 3),
+                       channel_row<PROBLEM, W>(p, inn, 5), passn, d1, k1, de);
+        int d2 = nearest<S>(L, k1, channel_row<PROBLEM, W>(p, inn, 4), passn, r);
+        if (need) {
+          mn[1] = (d1 >= 0 && d2 >= 0) ? d1 + d2 : 0;
+          mn[2] = de < 0 ? 0 : de;
+        }
+      }
+    }
+    // reward = sum over metrics, in index order, of weight * (old loss - new loss)
+    if (changed) {
+      const int4* tv = reinterpret_cast<const int4*>(a.targets + (size_t)env * kMaxMetrics * 2);
+      int tg[2 * ((PR::M + 1) / 2 * 2)];
+#pragma unroll
+      for (int q = 0; q < (2 * PR::M + 3) / 4; ++q) {
+        int4 t = tv[q];
+        tg[4 * q + 0] = t.x;
+        tg[4 * q + 1] = t.y;
+        tg[4 * q + 2] = t.z;
+        tg[4 * q + 3] = t.w;
+      }
+#pragma unroll
+      for (int i = 0; i < PR::M; ++i) {
+        int dl = loss(mo[i], tg[2 * i], tg[2 * i + 1]) - loss(mn[i], tg[2 * i], tg[2 * i + 1]);
+        reward = __fadd_rn(reward, __fmul_rn(a.weights[i], (float)dl));
+      }
+    }
+  }
+
+  // ---- bookkeeping
+  er.t += 1;
+  er.n_changes += changed ? 1 : 0;
+  const bool done = (er.t >= a.max_steps) || (a.max_changes > 0 && er.n_changes >= a.max_changes);
+  const bool restart = valid && done && a.autoreset != 0;
+  if (wave_any<S>(restart)) {
+    // fresh seeded episode for the finished levels; the others keep their registers
+    W np[PR::P], nfz;
+    int nh, nw, npy, npx;
+    uint64_t nkey = env_key(a.seed, (uint64_t)env, (uint64_t)(er.episode + 1));
+    begin_episode<S, PROBLEM>(a, L, nkey, np, nfz, nh, nw, npy, npx);
+    W ninside = inside_row<W>(L.y, nh, nw);
+    int nm[PR::M];
+    full_metrics<S, PROBLEM>(L, np, ninside, restart, nm);
+    if (restart) {
+#pragma unroll
+      for (int i = 0; i < PR::P; ++i) {
+        p[i] = np[i];
+        planes[(size_t)i * a.plane_stride + ridx] = np[i];
+      }
+      frozen[ridx] = nfz;
+#pragma unroll
+      for (int i = 0; i < PR::M; ++i) mn[i] = nm[i];
+      inside = ninside;
+      h = nh;
+      w = nw;
+      py = npy;
+      px = npx;
+      er.key = nkey;
+      er.episode += 1;
+      er.t = 0;
+      er.n_changes = 0;
+    }
+  }
+  if (!restart) {
+    if (a.pos_mode == kPosScan) {
+      px += 1;
+      if (px >= w) {
+        px = 0;
+        py += 1;
+        if (py >= h) py = 0;
+      }
+    } else {
+      uint64_t u = draw(er.key, 3, (uint32_t)er.t);
+      py = below((uint32_t)(u >> 32), h);
+      px = below((uint32_t)u, w);
+    }
+  }
+
+  // ---- store
+  if (valid && L.y == 0) {
+    er.h = (uint8_t)h;
+    er.w = (uint8_t)w;
+    er.py = (uint8_t)py;
+    er.px = (uint8_t)px;
+    a.env[env] = er;
+    if (changed || restart) store_metrics<S, PROBLEM>(a.metrics + (size_t)env * kMaxMetrics, mn);
+    if (a.reward) a.reward[env] = reward;
+    if (a.done) a.done[env] = done ? 1 : 0;
+  }
+
+  // ---- observation around the new position
+  if (a.obs != nullptr) write_obs<S, PROBLEM>(a, L, lds, p, inside, py, px, env0, nvalid);
+}
+
+// ------------------------------------------------- plain-layout conversion
+
+// tiles int8 [B][max_h][max_w] <-> bit-planes; one thread per (env, row).
+template <typename W>
+__global__ void set_state_kernel(KArgs a, int S, int P, int K, const int8_t* tiles,
+                                 const uint8_t* fro, const int16_t* hw, const int16_t* pos) {
+  int idx = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+  if (idx >= a.B * S) return;
+  int env = idx / S, y = idx % S;
+  int h = min(max((int)hw[2 * env], 1), a.max_h), w = min(max((int)hw[2 * env + 1], 1), a.max_w);
+  W pl[3] = {0, 0, 0};
+  W fz = 0;
+  if (y < h) {
+    for (int x = 0; x < w; ++x) {
+      size_t ci = ((size_t)env * a.max_h + y) * a.max_w + x;
+      int t = tiles[ci];
+      if (t < 0 || t >= K) t = 0;
+      for (int i = 0; i < P; ++i) pl[i] |= (W)((t >> i) & 1) << x;
+      if (fro && fro[ci]) fz |= (W)1 << x;
+    }
+  }
+  W* planes = reinterpret_cast<W*>(a.planes);
+  for (int i = 0; i < P; ++i) planes[(size_t)i * a.plane_stride + idx] = pl[i];
+  reinterpret_cast<W*>(a.frozen)[idx] = fz;
+  if (y == 0) {
+    EnvRec er = a.env[env];
+    er.h = (uint8_t)h;
+    er.w = (uint8_t)w;
+    er.py = (uint8_t)min(max((int)pos[2 * env], 0), h - 1);
+    er.px = (uint8_t)min(max((int)pos[2 * env + 1], 0), w - 1);
+    er.t = 0;
+    er.n_changes = 0;
+    a.env[env] = er;
+  }
+}
+
+template <typename W>
+__global__ void get_state_kernel(KArgs a, int S, int P, int8_t* tiles, uint8_t* fro, int16_t* hw,
+                                 int16_t* pos, int32_t* counters) {
+  int idx = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+  if (idx >= a.B * S) return;
+  int env = idx / S, y = idx % S;
+  EnvRec er = a.env[env];
+  const W* planes = reinterpret_cast<const W*>(a.planes);
+  W pl[3] = {0, 0, 0};
+  for (int i = 0; i < P; ++i) pl[i] = planes[(size_t)i * a.plane_stride + idx];
+  W fz = reinterpret_cast<const W*>(a.frozen)[idx];
+  if (y < a.max_h) {
+    for (int x = 0; x < a.max_w; ++x) {
+      size_t ci = ((size_t)env * a.max_h + y) * a.max_w + x;
+      bool in = y < er.h && x < er.w;
+      int t = 0;
+      for (int i = 0; i < P; ++i) t |= (int)((pl[i] >> x) & 1) << i;
+      if (tiles) tiles[ci] = in ? (int8_t)t : (int8_t)-1;
+      if (fro) fro[ci] = (in && ((fz >> x) & 1)) ? 1 : 0;
+    }
+  }
+  if (y == 0) {
+    if (hw) {
+      hw[2 * env] = er.h;
+      hw[2 * env + 1] = er.w;
+    }
+    if (pos) {
+      pos[2 * env] = er.py;
+      pos[2 * env + 1] = er.px;
+    }
+    if (counters) {
+      counters[3 * env] = er.t;
+      counters[3 * env + 1] = er.n_changes;
+      counters[3 * env + 2] = er.episode;
+    }
+  }
+}
+
+__global__ void copy_metrics_kernel(const int32_t* src, int32_t* dst, int B, int M) {
+  int idx = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+  if (idx >= B * M) return;
+  dst[idx] = src[(size_t)(idx / M) * kMaxMetrics + idx % M];
+}
+
+__global__ void set_targets_kernel(const int32_t* src, int32_t* dst, int B, int M) {
+  int idx = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+  if (idx >= B * M * 2) return;
+  int env = idx / (2 * M), r = idx % (2 * M);
+  dst[(size_t)env * kMaxMetrics * 2 + r] = src[idx];
+}
+
+// Cross-lane exchange check: the DPP shifts against the plain shuffle definition.
+__global__ __launch_bounds__(64) void selftest_kernel(int32_t* mismatches) {
+  int lane = (int)(threadIdx.x & 63u);
+  uint32_t v32 = 0x9E3779B9u * (uint32_t)(lane + 1);
+  uint64_t v64 = mix64((uint64_t)lane + 17);
+  int bad = 0;
+  {
+    Lanes<16> L;
+    uint32_t up = __shfl_up(v32, 1), dn = __shfl_down(v32, 1);
+    bad += L.from_above(v32) != (L.y == 0 ? 0u : up);
+    bad += L.from_below(v32) != (L.y == 15 ? 0u : dn);
+  }
+  {
+    Lanes<32> L;
+    uint32_t up = __shfl_up(v32, 1), dn = __shfl_down(v32, 1);
+    bad += L.from_above(v32) != (L.y == 0 ? 0u : up);
+    bad += L.from_below(v32) != (L.y == 31 ? 0u : dn);
+  }
+  {
+    Lanes<64> L;
+    uint64_t up = __shfl_up(v64, 1), dn = __shfl_down(v64, 1);
+    bad += L.from_above(v64) != (L.y == 0 ? 0ull : up);
+    bad += L.from_below(v64) != (L.y == 63 ? 0ull : dn);
+  }
+  if (bad) atomicAdd(mismatches, bad);
+}
+
+}  // namespace pcgrl

@@ -1,0 +1,70 @@
+"""Shared driver of the GPU-vs-oracle parity tests: same seeded config and actions on both sides,
+element-by-element comparison of everything a step returns."""
+import numpy as np
+import torch
+
+import oracle
+from paper_2408_12525_amd import binding, workloads as wl
+
+
+def assert_same(name, got, want, ctx):
+    got = got.cpu().numpy() if isinstance(got, torch.Tensor) else np.asarray(got)
+    if got.shape != want.shape or not np.array_equal(got, want):
+        bad = np.argwhere(got != want)
+        first = tuple(bad[0]) if len(bad) else None
+        raise AssertionError(f"{name} differs ({len(bad)} elements) {ctx}; first at {first}: "
+                             f"gpu={got[first] if first else None} oracle={want[first] if first else None}")
+
+
+def run_parity(cfg, steps, seed=1, aseed=2, bad_fraction=0.0, check_every=1, state_every=25,
+               env_slice=None, targets=None, label=""):
+    """Steps both implementations `steps` times.  Observations, rewards, done flags and metrics
+    are compared every `check_every` steps (all envs, or `env_slice` of them); the plain-layout
+    state every `state_every` steps and at the end.  Rewards must agree to 1e-6 absolute (they
+    are bit-equal when the weights are small integers)."""
+    print(f"[parity] {label} cfg={ {k: cfg[k] for k in ('problem','batch','max_h','max_w','min_h','obs_w','pad_mode','pos_mode','n_frozen','max_steps','regions_mode')} } steps={steps}", flush=True)
+    dev = torch.device("cuda", 0)
+    gpu = binding.Pcgrl(cfg, 0)
+    cpu = oracle.Oracle(cfg)
+    B = cfg["batch"]
+    sl = slice(None) if env_slice is None else env_slice
+    obs = gpu.new_obs()
+    rew = torch.empty(B, dtype=torch.float32, device=dev)
+    done = torch.empty(B, dtype=torch.uint8, device=dev)
+    gpu.pcgrl_reset(seed, obs)
+    want_obs = cpu.reset(seed)
+    if targets is not None:
+        gpu.pcgrl_set_targets(torch.from_numpy(targets).to(dev))
+        cpu.set_targets(targets)
+    assert_same("obs", obs[sl], want_obs[sl], "after reset")
+    assert_same("metrics", gpu.pcgrl_metrics()[sl], cpu.metrics()[sl], "after reset")
+    compare_state(gpu, cpu, "after reset")
+    acts = wl.random_actions(cfg, aseed, steps, bad_fraction)
+    acts_dev = torch.from_numpy(acts).to(dev)
+    for t in range(steps):
+        gpu.pcgrl_step(acts_dev[t], obs, rew, done)
+        check = (t % check_every == 0) or t == steps - 1
+        o, r, d = cpu.step(acts[t], want_obs=check)
+        if check:
+            ctx = f"at step {t}"
+            assert_same("done", done[sl], d[sl], ctx)
+            assert_same("metrics", gpu.pcgrl_metrics()[sl], cpu.metrics()[sl], ctx)
+            g = rew.cpu().numpy()
+            bad = np.flatnonzero(~(np.abs(g[sl] - r[sl]) <= 1e-6))
+            assert len(bad) == 0, (f"reward differs {ctx} in {len(bad)} envs; first env {bad[0]}: "
+                                   f"gpu={g[sl][bad[0]]} oracle={r[sl][bad[0]]}")
+            assert_same("obs", obs[sl], o[sl], ctx)
+        if t % state_every == 0 or t == steps - 1:
+            compare_state(gpu, cpu, f"at step {t}")
+    if bad_fraction > 0:
+        K = wl.NUM_TILES[cfg["problem"]]
+        assert gpu.pcgrl_bad_action_count() == int(((acts < 0) | (acts >= K)).sum())
+    torch.cuda.synchronize()
+    gpu.close()
+
+
+def compare_state(gpu, cpu, ctx):
+    g = gpu.pcgrl_get_state()
+    c = cpu.get_state()
+    for k in ("hw", "pos", "counters", "tiles", "frozen"):
+        assert_same(k, g[k], c[k], ctx)

@@ -1,0 +1,150 @@
+"""GPU library vs CPU oracle, through the C ABI, on the same seeded inputs (needs an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+import levels
+import oracle
+from parity import assert_same, compare_state, run_parity
+from paper_2408_12525_amd import binding, workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def test_lane_exchange_selftest():
+    assert binding.pcgrl_selftest(0) == 0
+
+
+SMALL = [
+    # label, config, steps, extra
+    ("binary16 walls-pad", wl.workload("binary16", batch=67, max_steps=40), 130, {}),
+    ("binary16 recount", wl.workload("binary16", batch=33, max_steps=50, regions_mode=wl.REGIONS_RECOUNT), 120, {}),
+    ("maze16", wl.workload("maze16", batch=130, max_steps=60), 150, {}),
+    ("maze16 scan+budget", wl.workload("maze16", batch=21, max_steps=300, pos_mode=wl.POS_SCAN, max_changes=25), 320, {}),
+    ("maze16 empty start, pinpoints", wl.make_config(wl.MAZE, 19, 16, 31, probs="empty", n_frozen=2, max_steps=70), 150, {}),
+    ("dungeon16 ow5", wl.make_config(wl.DUNGEON, 26, 13, 5, min_size=5, max_steps=45, n_frozen=3,
+                                      probs=[.40, .40, .04, .04, .04, .04, .04]), 140, {}),
+    ("binary32 rand ow3", wl.workload("binary32_rand_ow3", batch=75, max_steps=50), 130, {}),
+    ("binary32 rand ow15", wl.workload("binary32_rand_ow15", batch=41, max_steps=50), 110, {}),
+    ("binary32 rand ow63", wl.workload("binary32_rand_ow63", batch=23, max_steps=50), 110, {}),
+    ("binary32 rand ow63 recount, bad actions", wl.workload("binary32_rand_ow63", batch=9, max_steps=50,
+                                                              regions_mode=wl.REGIONS_RECOUNT), 110, dict(bad_fraction=0.1)),
+    ("maze32 even window", wl.make_config(wl.MAZE, 37, 24, 8, min_size=9, max_w=31, min_w=9, max_steps=64,
+                                          probs=[.45, .45, .05, .05]), 140, {}),
+    ("dungeon32", wl.workload("dungeon32", batch=45, max_steps=60), 130, {}),
+    ("dungeon32 uniform tiles, wall pad", wl.make_config(wl.DUNGEON, 18, 32, 15, pad_mode=wl.PAD_WALL, max_steps=80), 120, {}),
+    ("maze64", wl.workload("maze64", batch=19, max_steps=60), 130, {}),
+    ("maze64 uniform tiles scan", wl.make_config(wl.MAZE, 5, 64, 31, pos_mode=wl.POS_SCAN, max_steps=200), 210, {}),
+    ("binary64 rand ow63", wl.make_config(wl.BINARY, 7, 64, 63, min_size=33, n_frozen=8, max_steps=90, probs=[.65, .35]), 200, {}),
+    ("binary64 sparse walls", wl.make_config(wl.BINARY, 6, 64, 31, max_steps=90, probs=[.8, .2]), 120, {}),
+    ("dungeon64 ow1", wl.make_config(wl.DUNGEON, 4, 40, 1, max_w=64, max_steps=90), 100, {}),
+    ("batch of one", wl.make_config(wl.MAZE, 1, 16, 31, max_steps=30), 70, {}),
+    ("no autoreset", wl.make_config(wl.BINARY, 10, 16, 7, max_steps=20, autoreset=0), 50, {}),
+]
+
+
+@pytest.mark.parametrize("label,cfg,steps,extra", SMALL, ids=[s[0] for s in SMALL])
+def test_small_configs_every_step(label, cfg, steps, extra):
+    run_parity(cfg, steps, label=label, **extra)
+
+
+def test_control_targets_and_fractional_weights():
+    # per-env target ranges and non-integer weights: rewards must still agree to 1e-6
+    cfg = wl.make_config(wl.DUNGEON, 32, 16, 9, max_steps=10**6, autoreset=0,
+                         weights=[0.37, 1.13, 0.71, 0.0, 0.05, 2.9, 3.3, 1.7, 0.9, 0.11])
+    rng = np.random.default_rng(0)
+    lo = rng.integers(0, 20, size=(32, 10))
+    hi = lo + rng.integers(0, 30, size=(32, 10))
+    run_parity(cfg, 200, targets=np.stack([lo, hi], axis=2).astype(np.int32), label="control targets")
+
+
+def test_set_state_with_hand_built_levels():
+    dev = torch.device("cuda", 0)
+    for name in levels.all_fixtures():
+        problem, tiles, expect = levels.load(name)
+        pid = levels.PROBLEM_ID[problem]
+        h, w = tiles.shape
+        size = max(h, w)
+        cfg = wl.make_config(pid, 3, size, 5, min_size=1, autoreset=0)
+        gpu = binding.Pcgrl(cfg, 0)
+        cpu = oracle.Oracle(cfg)
+        gpu.pcgrl_reset(5)
+        cpu.reset(5)
+        buf = np.full((3, size, size), -1, np.int8)
+        buf[:, :h, :w] = tiles
+        fro = np.zeros((3, size, size), np.uint8)
+        fro[1, 0, 0] = 1
+        hw = np.array([[h, w]] * 3, np.int16)
+        pos = np.array([[0, 0], [0, 0], [h - 1, w - 1]], np.int16)
+        gpu.pcgrl_set_state(*(torch.from_numpy(a).to(dev) for a in (buf, fro, hw, pos)))
+        cpu.set_state(buf, fro, hw, pos)
+        m = gpu.pcgrl_metrics().cpu().numpy()
+        got = dict(zip(wl.metric_names(pid), (int(v) for v in m[0])))
+        for k, v in expect.items():
+            assert got[k] == v, (name, k, got)
+        assert_same("metrics", m, cpu.metrics(), name)
+        assert_same("obs", gpu.pcgrl_observe(), cpu.observe(), name)
+        compare_state(gpu, cpu, name)
+        # a few edits on top, including one on the frozen cell of env 1
+        K = wl.NUM_TILES[pid]
+        rew = torch.empty(3, dtype=torch.float32, device=dev)
+        for t in range(6):
+            a = np.array([(t + 1) % K, (t + 1) % K, t % K], np.int32)
+            gpu.pcgrl_step(torch.from_numpy(a).to(dev), None, rew, None)
+            _, r, _ = cpu.step(a, want_obs=False)
+            assert np.array_equal(rew.cpu().numpy(), r), (name, t)
+            assert_same("metrics", gpu.pcgrl_metrics(), cpu.metrics(), (name, t))
+        gpu.close()
+
+
+FULL = [
+    ("binary16", 64, 60, None),
+    ("maze16", 4096, 24, None),
+    ("binary32_rand_ow3", 16384, 12, None),
+    ("binary32_rand_ow15", 16384, 12, None),
+    ("binary32_rand_ow63", 16384, 8, slice(0, 16384, 7)),
+    ("maze64", 8192, 8, None),
+    ("dungeon32", 16384, 10, None),
+]
+
+
+@pytest.mark.parametrize("name,batch,steps,sl", FULL, ids=[f[0] for f in FULL])
+def test_full_size_workloads(name, batch, steps, sl):
+    """The benchmark's launch configuration (full batch, default modes), compared with the oracle
+    on every env for a few steps."""
+    cfg = wl.workload(name, batch=batch)
+    run_parity(cfg, steps, seed=0, aseed=1, env_slice=sl, state_every=steps, label=name + " full size")
+
+
+def test_results_do_not_depend_on_batch_partition():
+    dev = torch.device("cuda", 0)
+    cfg = wl.workload("maze16", batch=64, max_steps=30)
+    acts = torch.from_numpy(wl.random_actions(cfg, 3, 70)).to(dev)
+    big = binding.Pcgrl(cfg, 0)
+    small = binding.Pcgrl(dict(cfg, batch=13), 0)
+    ob, os_ = big.new_obs(), small.new_obs()
+    big.pcgrl_reset(9, ob)
+    small.pcgrl_reset(9, os_)
+    for t in range(70):
+        big.pcgrl_step(acts[t], ob)
+        small.pcgrl_step(acts[t, :13].contiguous(), os_)
+        assert torch.equal(ob[:13], os_)
+    assert torch.equal(big.pcgrl_metrics()[:13], small.pcgrl_metrics())
+    big.close()
+    small.close()
+
+
+def test_argument_errors_are_reported_not_raised_by_the_gpu():
+    bad = wl.workload("maze16", batch=4)
+    for field, val in (("obs_w", 64), ("max_h", 65), ("batch", 0), ("problem", 3), ("n_frozen", 9),
+                       ("min_h", 17), ("max_steps", 0), ("pad_mode", 2)):
+        with pytest.raises(binding.PcgrlError):
+            binding.Pcgrl(dict(bad, **{field: val}), 0)
+    env = binding.Pcgrl(bad, 0)
+    with pytest.raises(binding.PcgrlError):
+        env.pcgrl_step(torch.zeros(5, dtype=torch.int32, device="cuda"))
+    with pytest.raises(binding.PcgrlError):
+        env.pcgrl_step(torch.zeros(4, dtype=torch.int64, device="cuda"))
+    assert env.L.pcgrl_step(env.h, None, None, None, None, None) == -1
+    assert env.L.pcgrl_step(None, None, None, None, None, None) == -1
+    env.close()

@@ -1,0 +1,54 @@
+"""Host-only checks of the C ABI: the built library exports what include/pcgrl.h declares, and
+its defaults agree with the workload tables.  No GPU call is made."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2408_12525_amd import binding, build, workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    src = open(os.path.join(ROOT, "include", "pcgrl.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(pcgrl_[a-z_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_entry_point():
+    if not os.path.exists(build.LIB):
+        pytest.fail("libpcgrl.so has not been built (python -m paper_2408_12525_amd.build)")
+    lib = C.CDLL(build.LIB)
+    names = header_functions()
+    assert {"pcgrl_create", "pcgrl_reset", "pcgrl_step", "pcgrl_metrics"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_library_is_newer_than_its_sources():
+    assert not build.is_stale()
+
+
+@pytest.mark.parametrize("problem", [wl.BINARY, wl.MAZE, wl.DUNGEON])
+def test_default_config_matches_workload_table(problem):
+    c = binding.pcgrl_config_default(problem)
+    w, lo, hi = wl.default_reward_table(problem)
+    M = wl.num_metrics(problem)
+    assert list(c.weights)[:M] == w and list(c.target_lo)[:M] == lo and list(c.target_hi)[:M] == hi
+    K = wl.NUM_TILES[problem]
+    cdf = list(c.init_cdf)
+    assert cdf[K - 1] == 2**32 - 1 and all(cdf[i] <= cdf[i + 1] for i in range(K - 1))
+
+
+def test_host_side_argument_errors_need_no_gpu():
+    L = binding.load()
+    assert L.pcgrl_create(None, None, 0) == -1
+    assert L.pcgrl_config_default(7, C.byref(binding.PcgrlConfig())) == -2
+    assert L.pcgrl_destroy(None) == 0
+    assert L.pcgrl_strerror(-2).decode().startswith("configuration")
+    h = C.c_void_p()
+    bad = binding.make_config(wl.workload("maze16", batch=4, obs_w=99))
+    assert L.pcgrl_create(C.byref(h), C.byref(bad), 0) == -2 and not h
