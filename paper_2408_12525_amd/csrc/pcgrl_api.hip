@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -16,7 +17,8 @@ struct pcgrl_ctx {
   int S, G, P, K, M, C;
   int B_pad, nwaves;
   size_t word_bytes;
-  size_t lds_bytes;
+  size_t lds_bytes;  // per wavefront
+  int wpb;           // wavefronts per workgroup
   KArgs base;  // device pointers and configuration, copied into every launch
   void* d_planes;
   void* d_frozen;
@@ -73,13 +75,15 @@ int dispatch(int S, int problem, A&&... args) {
 
 template <int S, int PROBLEM> struct LaunchStep {
   static int run(const pcgrl_ctx* ctx, const KArgs& a, hipStream_t st) {
-    hipLaunchKernelGGL((step_kernel<S, PROBLEM>), dim3(ctx->nwaves), dim3(64), ctx->lds_bytes, st, a);
+    hipLaunchKernelGGL((step_kernel<S, PROBLEM>), dim3((ctx->nwaves + ctx->wpb - 1) / ctx->wpb),
+                       dim3(64 * ctx->wpb), ctx->lds_bytes * ctx->wpb, st, a);
     return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
   }
 };
 template <int S, int PROBLEM> struct LaunchInit {
   static int run(const pcgrl_ctx* ctx, const KArgs& a, hipStream_t st) {
-    hipLaunchKernelGGL((init_kernel<S, PROBLEM>), dim3(ctx->nwaves), dim3(64), ctx->lds_bytes, st, a);
+    hipLaunchKernelGGL((init_kernel<S, PROBLEM>), dim3((ctx->nwaves + ctx->wpb - 1) / ctx->wpb),
+                       dim3(64 * ctx->wpb), ctx->lds_bytes * ctx->wpb, st, a);
     return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
   }
 };
@@ -188,6 +192,11 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
     delete ctx;
     return PCGRL_E_CONFIG;
   }
+  ctx->wpb = 1;
+  if (const char* e = std::getenv("PCGRL_WPB")) {
+    int v = std::atoi(e);
+    if (v >= 1 && v <= 8 && ctx->lds_bytes * v <= 64 * 1024) ctx->wpb = v;
+  }
 
   const size_t rows = (size_t)ctx->B_pad * ctx->S;
   struct { void** p; size_t n; } allocs[] = {
@@ -231,6 +240,8 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   a.autoreset = cfg->autoreset;
   a.regions_mode = cfg->regions_mode;
   a.env_obs_bytes = (int32_t)E;
+  a.nwaves = ctx->nwaves;
+  a.lds_words = (int32_t)(ctx->lds_bytes / 4);
   for (int k = 0; k < 8; ++k) a.cdf[k] = cfg->init_cdf[k];
   for (int i = 0; i < kMaxMetrics; ++i) {
     a.weights[i] = cfg->weights[i];

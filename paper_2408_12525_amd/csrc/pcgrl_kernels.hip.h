@@ -16,6 +16,7 @@
 namespace pcgrl {
 
 constexpr int kMaxMetrics = 16;
+constexpr int kMaxBlock = 512;  // up to 8 independent wavefronts per workgroup
 
 enum : int { kBinary = 0, kMaze = 1, kDungeon = 2 };
 enum : int { kPadBorder = 0, kPadWall = 1 };
@@ -50,6 +51,8 @@ struct KArgs {
   int32_t max_h, max_w, min_h, min_w;
   int32_t obs_w, pad_mode, pos_mode, n_frozen, max_steps, max_changes, autoreset, regions_mode;
   int32_t env_obs_bytes;  // C * obs_w * obs_w
+  int32_t nwaves;         // wavefronts that have work
+  int32_t lds_words;      // LDS words of one wavefront's staging area
   int32_t flags;          // init kernel only
   uint32_t cdf[8];
   float weights[kMaxMetrics];
@@ -557,13 +560,17 @@ __device__ __forceinline__ void store_metrics(int32_t* dst, const int (&m)[Prob<
 // loading the stored level, recomputing all metrics, restoring default targets, writing the
 // observation.
 template <int S, int PROBLEM>
-__global__ __launch_bounds__(64) void init_kernel(KArgs a) {
+__global__ __launch_bounds__(kMaxBlock) void init_kernel(KArgs a) {
   using W = typename RowWord<S>::T;
   using PR = Prob<PROBLEM>;
-  extern __shared__ uint32_t lds[];
+  extern __shared__ uint32_t lds_all[];
   Lanes<S> L;
   constexpr int G = 64 / S;
-  const int env0 = (int)blockIdx.x * G;
+  const int wave_in_block = (int)(threadIdx.x >> 6);
+  const int wave = (int)blockIdx.x * (int)(blockDim.x >> 6) + wave_in_block;
+  if (wave >= a.nwaves) return;  // whole wavefronts leave; no block-wide barrier is used
+  uint32_t* lds = lds_all + (size_t)wave_in_block * a.lds_words;
+  const int env0 = wave * G;
   const int env = env0 + L.g;
   const bool valid = env < a.B;
   const int nvalid = min(G, a.B - env0);
@@ -614,13 +621,17 @@ __global__ __launch_bounds__(64) void init_kernel(KArgs a) {
 
 // One environment step of every level (see pcgrl_step in the public header).
 template <int S, int PROBLEM>
-__global__ __launch_bounds__(64) void step_kernel(KArgs a) {
+__global__ __launch_bounds__(kMaxBlock) void step_kernel(KArgs a) {
   using W = typename RowWord<S>::T;
   using PR = Prob<PROBLEM>;
-  extern __shared__ uint32_t lds[];
+  extern __shared__ uint32_t lds_all[];
   Lanes<S> L;
   constexpr int G = 64 / S;
-  const int env0 = (int)blockIdx.x * G;
+  const int wave_in_block = (int)(threadIdx.x >> 6);
+  const int wave = (int)blockIdx.x * (int)(blockDim.x >> 6) + wave_in_block;
+  if (wave >= a.nwaves) return;  // whole wavefronts leave; no block-wide barrier is used
+  uint32_t* lds = lds_all + (size_t)wave_in_block * a.lds_words;
+  const int env0 = wave * G;
   const int env = env0 + L.g;
   const bool valid = env < a.B;
   const int nvalid = min(G, a.B - env0);
