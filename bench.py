@@ -105,6 +105,8 @@ def main():
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--reps", type=int, default=3, help="timed repetitions of the K steps; the median is reported")
     ap.add_argument("--regions", choices=["incremental", "recount"], default="incremental")
+    ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
+                    help="replay a HIP graph of pcgrl_step launches (default) or call it from Python")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run 20 plain device copies of MIB MiB (the known "
@@ -142,9 +144,29 @@ def main():
     rew = torch.empty(B, dtype=torch.float32, device=dev)
     done = torch.empty(B, dtype=torch.uint8, device=dev)
     seed, aseed = 0, 1
-    n_act = min(K, 2048)   # the action stream repeats after 2048 steps (keeps it small in HBM)
+    n_act = min(K, 1000)   # the action stream repeats after 1000 steps (keeps it small in HBM)
     acts = torch.from_numpy(wl.random_actions(cfg, aseed, n_act)).to(dev)
     warm = torch.from_numpy(wl.random_actions(cfg, aseed + 1, max(W, 1))).to(dev)
+
+    # One HIP graph holds `chunk` consecutive pcgrl_step launches (each a kernel node with its own
+    # slice of the action stream); replaying it is how a launch-bound loop is meant to be driven
+    # on this hardware.  --launch eager calls pcgrl_step from Python instead (about 9 us of host
+    # time per call, which then bounds small batches).
+    chunk = min(n_act, K)
+    while K % chunk:
+        chunk -= 1
+    graph = None
+    if args.launch == "graph":
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            env.pcgrl_reset(seed, obs)
+            with torch.cuda.graph(graph, stream=side):
+                for t in range(chunk):
+                    env.pcgrl_step(acts[t], obs, rew, done)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
 
     times_ms, ev_ms = [], []
     for rep in range(args.reps):
@@ -155,9 +177,13 @@ def main():
         e1 = torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        e0.record()                      # on the current stream, the one the library launches on
-        for t in range(K):
-            env.pcgrl_step(acts[t % n_act], obs, rew, done)
+        e0.record()                      # on the current stream, the one the steps run on
+        if graph is not None:
+            for _ in range(K // chunk):
+                graph.replay()
+        else:
+            for t in range(K):
+                env.pcgrl_step(acts[t % n_act], obs, rew, done)
         e1.record()
         torch.cuda.synchronize()
         times_ms.append((time.perf_counter() - t0) * 1e3)
@@ -182,7 +208,7 @@ def main():
                    "batch": B, "map": f"{cfg['max_h']}x{cfg['max_w']}",
                    "min_map": f"{cfg['min_h']}x{cfg['min_w']}", "obs_w": cfg["obs_w"],
                    "obs_bytes_per_env": wl.obs_bytes(cfg), "n_frozen": cfg["n_frozen"],
-                   "regions": args.regions, "launches_per_step": 1, "reps": args.reps,
+                   "regions": args.regions, "launch": args.launch, "launches_per_step": 1, "reps": args.reps,
                    "algorithmic_bytes_per_env_step": abytes},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_from_profiles(tag),

@@ -86,6 +86,9 @@ typedef struct {
                            the same step; reward and done describe the finished transition, the
                            observation and cached metrics the new episode's first state */
   int32_t regions_mode; /* PCGRL_REGIONS_*; both give the same counts */
+  int32_t levels_per_wave; /* tuning only, results do not depend on it: 0 = automatic; 1, 2 or 4 =
+                           how many levels share one 64-lane wavefront (at most 64 / S, S = 16, 32
+                           or 64 covering max_h and max_w; larger requests are rounded down) */
   uint32_t init_cdf[PCGRL_MAX_TILES]; /* non-decreasing cumulative tile probabilities scaled by
                            2^32 (entry k = P(tile <= k)); the last tile takes the rest; all zero =
                            start from an all-empty map                      (Methods / Task) */

@@ -13,7 +13,11 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace pcgrl {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMaxMetrics = 16;
 constexpr int kMaxBlock = 512;  // up to 8 independent wavefronts per workgroup
@@ -52,6 +56,8 @@ struct KArgs {
   int32_t obs_w, pad_mode, pos_mode, n_frozen, max_steps, max_changes, autoreset, regions_mode;
   int32_t env_obs_bytes;  // C * obs_w * obs_w
   int32_t nwaves;         // wavefronts that have work
+  int32_t envs_per_wave;  // distinct levels per wavefront: a divisor of 64 / S
+  int32_t stream_obs;     // non-zero: write observations with non-temporal stores
   int32_t lds_words;      // LDS words of one wavefront's staging area
   int32_t flags;          // init kernel only
   uint32_t cdf[8];
@@ -142,14 +148,28 @@ template <int S> struct Lanes {
   __device__ __forceinline__ bool gany(bool pred) const {
     return gbits(__builtin_amdgcn_ballot_w64(pred)) != 0;
   }
+  // rotate by N lanes inside each row of 16 lanes / exchange with the lane 16 away
+  template <int N> static __device__ __forceinline__ int ror(int v) {
+    return __builtin_amdgcn_update_dpp(v, v, 0x120 + N, 0xf, 0xf, false);
+  }
+  static __device__ __forceinline__ int xor16(int v) { return __builtin_amdgcn_ds_swizzle(v, 0x401F); }
+  // sum / maximum over the lanes of the group, returned in every lane
   __device__ __forceinline__ int gsum(int v) const {
-#pragma unroll
-    for (int o = S / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    v += ror<8>(v);
+    v += ror<4>(v);
+    v += ror<2>(v);
+    v += ror<1>(v);
+    if constexpr (S >= 32) v += xor16(v);
+    if constexpr (S == 64) v = __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 32);
     return v;
   }
   __device__ __forceinline__ int gmax(int v) const {
-#pragma unroll
-    for (int o = S / 2; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o));
+    v = max(v, ror<8>(v));
+    v = max(v, ror<4>(v));
+    v = max(v, ror<2>(v));
+    v = max(v, ror<1>(v));
+    if constexpr (S >= 32) v = max(v, xor16(v));
+    if constexpr (S == 64) v = max(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 32));
     return v;
   }
   // value of lane `row` of this group
@@ -197,17 +217,22 @@ __device__ __forceinline__ int sweep(const Lanes<S>& L, typename RowWord<S>::T s
   using W = typename RowWord<S>::T;
   W V = seed, lastN = seed;
   int it = 0, last_it = 0;
-  for (;;) {
-    ++it;
-    W Vn = L.dilate(V) & pass;
-    W N = Vn ^ V;
-    bool ch = N != 0;
-    if (ch) {
-      lastN = N;
-      last_it = it;
+  for (;;) {  // two layers per convergence test
+    W V1 = L.dilate(V) & pass;
+    W N1 = V1 ^ V;
+    W V2 = L.dilate(V1) & pass;
+    W N2 = V2 ^ V1;
+    if (N1 != 0) {
+      lastN = N1;
+      last_it = it + 1;
     }
-    V = Vn;
-    if (!wave_any<S>(ch)) break;
+    if (N2 != 0) {
+      lastN = N2;
+      last_it = it + 2;
+    }
+    it += 2;
+    V = V2;
+    if (!wave_any<S>(N2 != 0)) break;
   }
   int d = L.gmax(last_it);
   last = last_it == d ? lastN : (W)0;
@@ -237,18 +262,20 @@ __device__ __forceinline__ int nearest(const Lanes<S>& L, typename RowWord<S>::T
   W V = src;
   int d = -1, it = 0;
   reached = 0;
-  for (;;) {
-    ++it;
-    W Vn = L.dilate(V) & pass;
-    bool ch = Vn != V;
-    uint64_t hit = L.gbits(__builtin_amdgcn_ballot_w64((Vn & tgt) != 0));
-    V = Vn;
-    if (hit != 0 && d < 0) {
-      d = it;
-      reached = Vn & tgt;
+  for (;;) {  // two layers per trip
+    W V1 = L.dilate(V) & pass;
+    W V2 = L.dilate(V1) & pass;
+    uint64_t h1 = L.gbits(__builtin_amdgcn_ballot_w64((V1 & tgt) != 0));
+    uint64_t h2 = L.gbits(__builtin_amdgcn_ballot_w64((V2 & tgt) != 0));
+    bool ch = V2 != V;
+    V = V2;
+    if (d < 0 && h2 != 0) {  // the target set is hit in the first layer whenever h1 says so
+      d = h1 != 0 ? it + 1 : it + 2;
+      reached = (h1 != 0 ? V1 : V2) & tgt;
       V = 0;
       pass = 0;
     }
+    it += 2;
     if (!wave_any<S>(ch && d < 0)) break;
   }
   return d;
@@ -266,18 +293,21 @@ __device__ __forceinline__ void nearest_two(const Lanes<S>& L, typename RowWord<
   d_a = -1;
   d_b = -1;
   reached_a = 0;
-  for (;;) {
-    ++it;
-    W Vn = L.dilate(V) & pass;
-    bool ch = Vn != V;
-    uint64_t hit_a = L.gbits(__builtin_amdgcn_ballot_w64((Vn & tgt_a) != 0));
-    uint64_t hit_b = L.gbits(__builtin_amdgcn_ballot_w64((Vn & tgt_b) != 0));
-    V = Vn;
-    if (hit_a != 0 && d_a < 0) {
-      d_a = it;
-      reached_a = Vn & tgt_a;
+  for (;;) {  // two layers per trip
+    W V1 = L.dilate(V) & pass;
+    W V2 = L.dilate(V1) & pass;
+    uint64_t a1 = L.gbits(__builtin_amdgcn_ballot_w64((V1 & tgt_a) != 0));
+    uint64_t a2 = L.gbits(__builtin_amdgcn_ballot_w64((V2 & tgt_a) != 0));
+    uint64_t b1 = L.gbits(__builtin_amdgcn_ballot_w64((V1 & tgt_b) != 0));
+    uint64_t b2 = L.gbits(__builtin_amdgcn_ballot_w64((V2 & tgt_b) != 0));
+    bool ch = V2 != V;
+    V = V2;
+    if (d_a < 0 && a2 != 0) {
+      d_a = a1 != 0 ? it + 1 : it + 2;
+      reached_a = (a1 != 0 ? V1 : V2) & tgt_a;
     }
-    if (hit_b != 0 && d_b < 0) d_b = it;
+    if (d_b < 0 && b2 != 0) d_b = b1 != 0 ? it + 1 : it + 2;
+    it += 2;
     bool finished = d_a >= 0 && d_b >= 0;
     if (finished) {
       V = 0;
@@ -301,7 +331,7 @@ __device__ __forceinline__ int regions_full(const Lanes<S>& L, typename RowWord<
     if (!wave_any<S>(V != 0)) break;
     count += L.gany(V != 0) ? 1 : 0;
     for (;;) {
-      W Vn = L.dilate(V) & R;
+      W Vn = L.dilate(L.dilate(V) & R) & R;
       bool ch = Vn != V;
       V = Vn;
       if (!wave_any<S>(ch)) break;
@@ -320,7 +350,12 @@ __device__ __forceinline__ int neighbour_components(const Lanes<S>& L, typename 
                                                     typename RowWord<S>::T passw) {
   using W = typename RowWord<S>::T;
   W U = nbr;
-  int left = L.gsum(popc(U));
+  // at most four cells in three rows; a row holds two of them only for the left/right pair
+  auto count = [&](W u) {
+    int rows = popc(L.gbits(__builtin_amdgcn_ballot_w64(u != 0)));
+    return rows + (L.gany((u & (u - 1)) != 0) ? 1 : 0);
+  };
+  int left = count(U);
   int k = 0;
   for (;;) {
     bool go = left >= 2;
@@ -334,7 +369,7 @@ __device__ __forceinline__ int neighbour_components(const Lanes<S>& L, typename 
     W pw = go ? passw : (W)0;
     k += go ? 1 : 0;
     for (;;) {
-      W Vn = L.dilate(V) & pw;
+      W Vn = L.dilate(L.dilate(V) & pw) & pw;
       bool ch = Vn != V;
       V = Vn;
       bool open = L.gany((U & ~V) != 0);  // some neighbour still unreached
@@ -346,7 +381,7 @@ __device__ __forceinline__ int neighbour_components(const Lanes<S>& L, typename 
       if (!wave_any<S>(ch && open)) break;
     }
     U &= ~V;
-    left = L.gsum(popc(U));
+    left = count(U);
   }
   return k;
 }
@@ -441,17 +476,36 @@ template <typename W> __device__ __forceinline__ W inside_row(int y, int h, int 
 
 // -------------------------------------------------------------- observation
 
-// Writes the observations of the up to G levels of this wavefront.  The window rows are first
-// packed as a bit stream in LDS (bit j of the stream = byte j of the wave's contiguous output
+// Orders this wavefront's LDS accesses (other lanes' writes before this lane's reads).  LDS
+// operations of one wavefront execute in issue order, so only the compiler has to be told; the
+// fence names the LDS address space so that no wait on global memory is generated.
+__device__ __forceinline__ void lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront", "local");
+  __builtin_amdgcn_wave_barrier();
+}
+
+// How the lane groups of a wavefront are used.  A wavefront has G = 64 / S groups; `epw` of them
+// carry distinct levels (slots), the remaining groups hold copies of those levels (copy > 0).
+// Copies repeat the metric work for free (their lanes would idle otherwise) and share out the
+// observation channels; only copy 0 stores results.  Small batches use fewer levels per wavefront
+// so that more wavefronts, and with them more latency hiding, are in flight.
+struct Slot {
+  int slot, copy, copies;
+};
+
+// Writes the observations of the `nvalid` levels of this wavefront.  The window rows are first
+// packed as a bit stream in LDS (bit j of the stream = byte j of the wavefront's contiguous output
 // region, shifted so that 16-bit chunks line up with 16-byte aligned addresses), then every lane
-// widens 16 bits to 16 bytes and issues one aligned 16-byte store.
-template <int S, int PROBLEM>
-__device__ __forceinline__ void write_obs(const KArgs& a, const Lanes<S>& L, uint32_t* lds,
+// widens 16 bits to 16 bytes and issues one aligned 16-byte store.  WIDE = window wider than 32.
+template <int S, int PROBLEM, bool WIDE>
+__device__ __forceinline__ void write_obs(const KArgs& a, const Lanes<S>& L, const Slot& sl,
+                                          uint32_t* lds,
                                           const typename RowWord<S>::T (&p)[Prob<PROBLEM>::P],
                                           typename RowWord<S>::T inside, int qy, int qx, int env0,
                                           int nvalid) {
   using W = typename RowWord<S>::T;
   using PR = Prob<PROBLEM>;
+  using BW = typename std::conditional<WIDE, uint64_t, uint32_t>::type;  // one window row
   const int ow = a.obs_w, r = ow >> 1;
   const int C = PR::K + (a.pad_mode == kPadBorder ? 1 : 0);
   const int E = a.env_obs_bytes;
@@ -460,68 +514,76 @@ __device__ __forceinline__ void write_obs(const KArgs& a, const Lanes<S>& L, uin
   const int total = d + nvalid * E;  // stream length in bits
   const int nwords = (total + 31) >> 5;
   for (int i = L.lane; i < nwords; i += 64) lds[i] = 0;
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
+  lds_sync();
 
-  if (L.g < nvalid) {
-    const uint64_t owmask = (1ull << ow) - 1ull;  // ow <= 63
+  if (sl.slot < nvalid) {
+    const BW owmask = WIDE ? (BW)((1ull << ow) - 1ull) : (BW)(0xffffffffu >> (32 - ow));
     const int y0 = qy - r, x0 = qx - r;
-    const int i_first = (L.y - y0) & (S - 1);
-    // part of the window row that lies outside the map's columns
-    uint64_t in64 = (uint64_t)inside;
-    uint64_t in_win = (x0 >= 0 ? (in64 >> x0) : (in64 << (-x0))) & owmask;
-    for (int i = i_first; i < ow; i += S) {
-      const bool real = (y0 + i) == L.y;
-      for (int c = 0; c < C; ++c) {
-        uint64_t bits;
-        if (real) {
-          if (c < PR::K) {
-            uint64_t row = (uint64_t)channel_row<PROBLEM, W>(p, inside, c);
-            bits = (x0 >= 0 ? (row >> x0) : (row << (-x0))) & owmask;
-            if (a.pad_mode == kPadWall && c == 1) bits |= ~in_win & owmask;
-          } else {
-            bits = ~in_win & owmask;
-          }
-        } else {
-          bool padc = a.pad_mode == kPadBorder ? (c == PR::K) : (c == 1);
-          bits = padc ? owmask : 0ull;
-        }
+    const int sr = x0 > 0 ? x0 : 0, sl_ = x0 < 0 ? -x0 : 0;  // one of the two shifts is zero
+    auto window = [&](W row) -> BW {
+      if constexpr (WIDE || S == 64) return (BW)(((uint64_t)row >> sr) << sl_) & owmask;
+      else return (BW)((row >> sr) << sl_) & owmask;
+    };
+    const BW out_win = (BW)~window(inside) & owmask;  // window cells outside the map's columns
+    const int padc = a.pad_mode == kPadBorder ? PR::K : 1;
+    const int cstride = ow * ow;
+    for (int i = (L.y - y0) & (S - 1); i < ow; i += S) {
+      const bool real = (y0 + i) == L.y;  // otherwise the row lies above or below the buffer
+      int off = d + sl.slot * E + i * ow + sl.copy * cstride;
+      for (int c = sl.copy; c < C; c += sl.copies, off += sl.copies * cstride) {
+        const BW in_map = c < PR::K ? window(channel_row<PROBLEM, W>(p, inside, c)) : (BW)0;
+        const BW pad_real = c == padc ? out_win : (BW)0, pad_all = c == padc ? owmask : (BW)0;
+        const BW bits = real ? (BW)(in_map | pad_real) : pad_all;
         if (bits != 0) {
-          int off = d + L.g * E + (c * ow + i) * ow;
-          int w0 = off >> 5, s = off & 31;
-          uint64_t lo = bits << s;
-          uint32_t hi = s ? (uint32_t)(bits >> (64 - s)) : 0u;
-          if ((uint32_t)lo) atomicOr(&lds[w0], (uint32_t)lo);
-          if ((uint32_t)(lo >> 32)) atomicOr(&lds[w0 + 1], (uint32_t)(lo >> 32));
-          if (hi) atomicOr(&lds[w0 + 2], hi);
+          const int w0 = off >> 5, sh = off & 31;
+          if constexpr (WIDE) {
+            uint64_t lo = bits << sh;
+            uint32_t hi = sh ? (uint32_t)(bits >> (64 - sh)) : 0u;
+            atomicOr(&lds[w0], (uint32_t)lo);
+            atomicOr(&lds[w0 + 1], (uint32_t)(lo >> 32));
+            if (hi) atomicOr(&lds[w0 + 2], hi);
+          } else {
+            uint64_t t = (uint64_t)bits << sh;
+            atomicOr(&lds[w0], (uint32_t)t);
+            if ((uint32_t)(t >> 32)) atomicOr(&lds[w0 + 1], (uint32_t)(t >> 32));
+          }
         }
       }
     }
   }
-  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-  __builtin_amdgcn_wave_barrier();
+  lds_sync();
 
   uint8_t* base = region - d;  // 16-byte aligned
-  const int nchunks = (total + 15) >> 4;
   const uint16_t* lds16 = reinterpret_cast<const uint16_t*>(lds);
-  for (int q = L.lane; q < nchunks; q += 64) {
-    uint32_t b = lds16[q];
+  auto widen = [&](uint32_t b) {
     uint4 v;
     v.x = __umul24(b & 15u, 0x00204081u) & 0x01010101u;
     v.y = __umul24((b >> 4) & 15u, 0x00204081u) & 0x01010101u;
     v.z = __umul24((b >> 8) & 15u, 0x00204081u) & 0x01010101u;
-    v.w = __umul24((b >> 12) & 15u, 0x00204081u) & 0x01010101u;
-    int lo = q << 4;
-    if (lo >= d && lo + 16 <= total) {
-      *reinterpret_cast<uint4*>(base + lo) = v;
-    } else {
-      uint32_t wds[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-      for (int t = 0; t < 16; ++t) {
-        int pos = lo + t;
-        if (pos >= d && pos < total) base[pos] = (uint8_t)((wds[t >> 2] >> ((t & 3) * 8)) & 0xffu);
-      }
+    v.w = __umul24(b >> 12, 0x00204081u) & 0x01010101u;
+    return v;
+  };
+  // chunks that lie completely inside the region: no bounds test, one aligned 16-byte store each
+  const int q_lo = (d + 15) >> 4, q_hi = total >> 4;
+  if (a.stream_obs) {
+    // the batch's observations exceed the last-level cache: stream them past it
+    for (int q = q_lo + L.lane; q < q_hi; q += 64) {
+      const uint4 v = widen(lds16[q]);
+      u32x4 nv = {v.x, v.y, v.z, v.w};
+      __builtin_nontemporal_store(nv, reinterpret_cast<u32x4*>(base + ((uint32_t)q << 4)));
     }
+  } else {
+    for (int q = q_lo + L.lane; q < q_hi; q += 64)
+      *reinterpret_cast<uint4*>(base + ((uint32_t)q << 4)) = widen(lds16[q]);
+  }
+  // the partial chunk at the head (lanes 0-15, one byte each) and at the tail (lanes 16-31)
+  {
+    const int t = L.lane & 15;
+    const bool is_tail = L.lane >= 16;
+    const int q = is_tail ? q_hi : 0;
+    const bool want = L.lane < 32 && (is_tail ? ((total & 15) != 0 && (q_hi > 0 || d == 0)) : d > 0);
+    const int pos = (q << 4) + t;
+    if (want && pos >= d && pos < total) base[pos] = (uint8_t)((lds16[q] >> t) & 1u);
   }
 }
 
@@ -556,6 +618,42 @@ __device__ __forceinline__ void store_metrics(int32_t* dst, const int (&m)[Prob<
   }
 }
 
+// Which wavefront, which levels: shared prologue of the two kernels.
+template <int S> struct WaveMap {
+  int wave, env0, nvalid, env, envl;
+  bool valid, primary;
+  Slot sl;
+  uint32_t* lds;
+  __device__ __forceinline__ bool init(const KArgs& a, const Lanes<S>& L, uint32_t* lds_all) {
+    constexpr int G = 64 / S;
+    const int wave_in_block = (int)(threadIdx.x >> 6);
+    wave = (int)blockIdx.x * (int)(blockDim.x >> 6) + wave_in_block;
+    if (wave >= a.nwaves) return false;  // whole wavefronts leave; no block-wide barrier is used
+    lds = lds_all + (size_t)wave_in_block * a.lds_words;
+    const int epw = G == 1 ? 1 : a.envs_per_wave;
+    sl.copies = G / epw;
+    sl.slot = G == 1 ? 0 : L.g % epw;
+    sl.copy = G == 1 ? 0 : L.g / epw;
+    env0 = wave * epw;
+    nvalid = min(epw, a.B - env0);
+    env = env0 + sl.slot;
+    valid = env < a.B;
+    primary = valid && sl.copy == 0;
+    envl = valid ? env : env0;  // an index that is always safe to load from
+    return true;
+  }
+};
+
+template <int S, int PROBLEM>
+__device__ __forceinline__ void observe(const KArgs& a, const Lanes<S>& L, const WaveMap<S>& wm,
+                                        const typename RowWord<S>::T (&p)[Prob<PROBLEM>::P],
+                                        typename RowWord<S>::T inside, int qy, int qx) {
+  if (a.obs_w > 32)
+    write_obs<S, PROBLEM, true>(a, L, wm.sl, wm.lds, p, inside, qy, qx, wm.env0, wm.nvalid);
+  else
+    write_obs<S, PROBLEM, false>(a, L, wm.sl, wm.lds, p, inside, qy, qx, wm.env0, wm.nvalid);
+}
+
 // Reset / refresh / observe: flags choose between generating a fresh episode 0 from the seed or
 // loading the stored level, recomputing all metrics, restoring default targets, writing the
 // observation.
@@ -565,24 +663,17 @@ __global__ __launch_bounds__(kMaxBlock) void init_kernel(KArgs a) {
   using PR = Prob<PROBLEM>;
   extern __shared__ uint32_t lds_all[];
   Lanes<S> L;
-  constexpr int G = 64 / S;
-  const int wave_in_block = (int)(threadIdx.x >> 6);
-  const int wave = (int)blockIdx.x * (int)(blockDim.x >> 6) + wave_in_block;
-  if (wave >= a.nwaves) return;  // whole wavefronts leave; no block-wide barrier is used
-  uint32_t* lds = lds_all + (size_t)wave_in_block * a.lds_words;
-  const int env0 = wave * G;
-  const int env = env0 + L.g;
-  const bool valid = env < a.B;
-  const int nvalid = min(G, a.B - env0);
+  WaveMap<S> wm;
+  if (!wm.init(a, L, lds_all)) return;
   W* planes = reinterpret_cast<W*>(a.planes);
   W* frozen = reinterpret_cast<W*>(a.frozen);
-  const size_t ridx = (size_t)env * S + L.y;  // inside the padded allocation even when !valid
+  const size_t ridx = (size_t)wm.envl * S + L.y;
 
   W p[PR::P], fz;
   int h, w, py, px;
   EnvRec er;
   if (a.flags & kInitGenerate) {
-    er.key = env_key(a.seed, (uint64_t)env, 0);
+    er.key = env_key(a.seed, (uint64_t)wm.envl, 0);
     er.t = 0;
     er.n_changes = 0;
     er.episode = 0;
@@ -592,12 +683,14 @@ __global__ __launch_bounds__(kMaxBlock) void init_kernel(KArgs a) {
     er.w = (uint8_t)w;
     er.py = (uint8_t)py;
     er.px = (uint8_t)px;
+    if (wm.primary) {
 #pragma unroll
-    for (int i = 0; i < PR::P; ++i) planes[(size_t)i * a.plane_stride + ridx] = p[i];
-    frozen[ridx] = fz;
-    if (L.y == 0) a.env[env] = er;
+      for (int i = 0; i < PR::P; ++i) planes[(size_t)i * a.plane_stride + ridx] = p[i];
+      frozen[ridx] = fz;
+      if (L.y == 0) a.env[wm.env] = er;
+    }
   } else {
-    er = a.env[env];
+    er = a.env[wm.envl];
     h = er.h;
     w = er.w;
     py = er.py;
@@ -608,15 +701,14 @@ __global__ __launch_bounds__(kMaxBlock) void init_kernel(KArgs a) {
   const W inside = inside_row<W>(L.y, h, w);
   if (a.flags & kInitMetrics) {
     int m[PR::M];
-    full_metrics<S, PROBLEM>(L, p, inside, valid, m);
-    if (L.y == 0) store_metrics<S, PROBLEM>(a.metrics + (size_t)env * kMaxMetrics, m);
+    full_metrics<S, PROBLEM>(L, p, inside, wm.valid, m);
+    if (wm.primary && L.y == 0) store_metrics<S, PROBLEM>(a.metrics + (size_t)wm.env * kMaxMetrics, m);
   }
-  if ((a.flags & kInitTargets) && L.y < PR::M) {
-    a.targets[((size_t)env * kMaxMetrics + L.y) * 2 + 0] = a.target_lo[L.y];
-    a.targets[((size_t)env * kMaxMetrics + L.y) * 2 + 1] = a.target_hi[L.y];
+  if ((a.flags & kInitTargets) && wm.primary && L.y < PR::M) {
+    a.targets[((size_t)wm.env * kMaxMetrics + L.y) * 2 + 0] = a.target_lo[L.y];
+    a.targets[((size_t)wm.env * kMaxMetrics + L.y) * 2 + 1] = a.target_hi[L.y];
   }
-  if ((a.flags & kInitObs) && a.obs != nullptr)
-    write_obs<S, PROBLEM>(a, L, lds, p, inside, py, px, env0, nvalid);
+  if ((a.flags & kInitObs) && a.obs != nullptr) observe<S, PROBLEM>(a, L, wm, p, inside, py, px);
 }
 
 // One environment step of every level (see pcgrl_step in the public header).
@@ -626,46 +718,82 @@ __global__ __launch_bounds__(kMaxBlock) void step_kernel(KArgs a) {
   using PR = Prob<PROBLEM>;
   extern __shared__ uint32_t lds_all[];
   Lanes<S> L;
-  constexpr int G = 64 / S;
-  const int wave_in_block = (int)(threadIdx.x >> 6);
-  const int wave = (int)blockIdx.x * (int)(blockDim.x >> 6) + wave_in_block;
-  if (wave >= a.nwaves) return;  // whole wavefronts leave; no block-wide barrier is used
-  uint32_t* lds = lds_all + (size_t)wave_in_block * a.lds_words;
-  const int env0 = wave * G;
-  const int env = env0 + L.g;
-  const bool valid = env < a.B;
-  const int nvalid = min(G, a.B - env0);
+  WaveMap<S> wm;
+  if (!wm.init(a, L, lds_all)) return;
+  const bool valid = wm.valid;
   W* planes = reinterpret_cast<W*>(a.planes);
   W* frozen = reinterpret_cast<W*>(a.frozen);
-  const size_t ridx = (size_t)env * S + L.y;
+  const size_t ridx = (size_t)wm.envl * S + L.y;
 
-  // ---- load
+  // ---- load: everything the step needs is requested up front (one memory round trip)
   W p[PR::P];
 #pragma unroll
   for (int i = 0; i < PR::P; ++i) p[i] = planes[(size_t)i * a.plane_stride + ridx];
-  EnvRec er = a.env[env];
-  int h = er.h, w = er.w, py = er.py, px = er.px;
-  const int act = valid ? a.actions[env] : -1;
-  const W fzrow = frozen[(size_t)env * S + py];
+  const W fz = frozen[ridx];
+  EnvRec er = a.env[wm.envl];
+  const int act = valid ? a.actions[wm.envl] : -1;
   int mo[PR::M];
-  load_metrics<S, PROBLEM>(a.metrics + (size_t)env * kMaxMetrics, mo);
+  load_metrics<S, PROBLEM>(a.metrics + (size_t)wm.envl * kMaxMetrics, mo);
+  constexpr int kTg = (2 * PR::M + 3) / 4 * 4;
+  int tg[kTg];
+  {
+    const int4* tv = reinterpret_cast<const int4*>(a.targets + (size_t)wm.envl * kMaxMetrics * 2);
+#pragma unroll
+    for (int q = 0; q < kTg / 4; ++q) {
+      int4 t = tv[q];
+      tg[4 * q + 0] = t.x;
+      tg[4 * q + 1] = t.y;
+      tg[4 * q + 2] = t.z;
+      tg[4 * q + 3] = t.w;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < kTg; ++i) asm volatile("" : "+v"(tg[i]));  // issue these loads here, not at their use
+  int h = er.h, w = er.w, py = er.py, px = er.px;
   W inside = inside_row<W>(L.y, h, w);
 
   // ---- edit (Methods / Training: the agent may change the tile it stands on)
+  const bool at_row = L.y == py;
   int old_code = 0;
 #pragma unroll
-  for (int i = 0; i < PR::P; ++i) old_code |= (int)((L.gread(p[i], py) >> px) & 1) << i;
+  for (int i = 0; i < PR::P; ++i) old_code |= (L.gany(at_row && ((p[i] >> px) & 1)) ? 1 : 0) << i;
+  const bool is_frozen = L.gany(at_row && ((fz >> px) & 1));
   const bool in_range = act >= 0 && act < PR::K;
-  const bool is_frozen = ((fzrow >> px) & 1) != 0;
   const bool changed = valid && in_range && !is_frozen && act != old_code;
-  if (valid && !in_range && L.y == 0) atomicAdd(a.bad_actions, 1ull);
-  if (changed && L.y == py) {
+  {
+    const uint64_t bad = __builtin_amdgcn_ballot_w64(wm.primary && !in_range && L.y == 0);
+    if (bad != 0 && L.lane == 0) atomicAdd(a.bad_actions, (unsigned long long)__popcll(bad));
+  }
+  if (changed && at_row) {
 #pragma unroll
     for (int i = 0; i < PR::P; ++i) {
       p[i] = (p[i] & ~((W)1 << px)) | ((W)((act >> i) & 1) << px);
-      planes[(size_t)i * a.plane_stride + ridx] = p[i];
+      if (wm.primary) planes[(size_t)i * a.plane_stride + ridx] = p[i];
     }
   }
+  // ---- counters, done flag and the agent's next cell need nothing but the edit
+  er.t += 1;
+  er.n_changes += changed ? 1 : 0;
+  const bool done = (er.t >= a.max_steps) || (a.max_changes > 0 && er.n_changes >= a.max_changes);
+  const bool restart = valid && done && a.autoreset != 0;
+  int qy = py, qx = px;
+  if (a.pos_mode == kPosScan) {
+    qx += 1;
+    if (qx >= w) {
+      qx = 0;
+      qy += 1;
+      if (qy >= h) qy = 0;
+    }
+  } else {
+    uint64_t u = draw(er.key, 3, (uint32_t)er.t);
+    qy = below((uint32_t)(u >> 32), h);
+    qx = below((uint32_t)u, w);
+  }
+  // ---- observation around the new position.  It is issued before the metrics so that its
+  // stores drain while the floods run; a wavefront in which some level restarts writes it last,
+  // from the new episode's level.
+  const bool any_restart = wave_any<S>(restart);
+  if (a.obs != nullptr && !any_restart) observe<S, PROBLEM>(a, L, wm, p, inside, qy, qx);
 
   // ---- metrics, only where the edit modified the map (Methods / Task)
   int mn[PR::M];
@@ -688,7 +816,7 @@ __global__ __launch_bounds__(kMaxBlock) void step_kernel(KArgs a) {
     } else {
       const bool flip = changed && was_pass != now_pass;
       if (wave_any<S>(flip)) {
-        W cell = (flip && L.y == py) ? (W)1 << px : (W)0;
+        W cell = (flip && at_row) ? (W)1 << px : (W)0;
         W passw = flip ? (pass & ~cell) : (W)0;
         W nbr = (L.dilate(cell) & ~cell) & passw;
         int k = neighbour_components<S>(L, nbr, passw);
@@ -723,16 +851,6 @@ __global__ __launch_bounds__(kMaxBlock) void step_kernel(KArgs a) {
     }
     // reward = sum over metrics, in index order, of weight * (old loss - new loss)
     if (changed) {
-      const int4* tv = reinterpret_cast<const int4*>(a.targets + (size_t)env * kMaxMetrics * 2);
-      int tg[2 * ((PR::M + 1) / 2 * 2)];
-#pragma unroll
-      for (int q = 0; q < (2 * PR::M + 3) / 4; ++q) {
-        int4 t = tv[q];
-        tg[4 * q + 0] = t.x;
-        tg[4 * q + 1] = t.y;
-        tg[4 * q + 2] = t.z;
-        tg[4 * q + 3] = t.w;
-      }
 #pragma unroll
       for (int i = 0; i < PR::M; ++i) {
         int dl = loss(mo[i], tg[2 * i], tg[2 * i + 1]) - loss(mn[i], tg[2 * i], tg[2 * i + 1]);
@@ -740,17 +858,11 @@ __global__ __launch_bounds__(kMaxBlock) void step_kernel(KArgs a) {
       }
     }
   }
-
-  // ---- bookkeeping
-  er.t += 1;
-  er.n_changes += changed ? 1 : 0;
-  const bool done = (er.t >= a.max_steps) || (a.max_changes > 0 && er.n_changes >= a.max_changes);
-  const bool restart = valid && done && a.autoreset != 0;
-  if (wave_any<S>(restart)) {
-    // fresh seeded episode for the finished levels; the others keep their registers
+  // ---- auto-reset: fresh seeded episode for the finished levels; the others keep their registers
+  if (any_restart) {
     W np[PR::P], nfz;
     int nh, nw, npy, npx;
-    uint64_t nkey = env_key(a.seed, (uint64_t)env, (uint64_t)(er.episode + 1));
+    uint64_t nkey = env_key(a.seed, (uint64_t)wm.envl, (uint64_t)(er.episode + 1));
     begin_episode<S, PROBLEM>(a, L, nkey, np, nfz, nh, nw, npy, npx);
     W ninside = inside_row<W>(L.y, nh, nw);
     int nm[PR::M];
@@ -759,51 +871,35 @@ __global__ __launch_bounds__(kMaxBlock) void step_kernel(KArgs a) {
 #pragma unroll
       for (int i = 0; i < PR::P; ++i) {
         p[i] = np[i];
-        planes[(size_t)i * a.plane_stride + ridx] = np[i];
+        if (wm.primary) planes[(size_t)i * a.plane_stride + ridx] = np[i];
       }
-      frozen[ridx] = nfz;
+      if (wm.primary) frozen[ridx] = nfz;
 #pragma unroll
       for (int i = 0; i < PR::M; ++i) mn[i] = nm[i];
       inside = ninside;
       h = nh;
       w = nw;
-      py = npy;
-      px = npx;
+      qy = npy;
+      qx = npx;
       er.key = nkey;
       er.episode += 1;
       er.t = 0;
       er.n_changes = 0;
     }
   }
-  if (!restart) {
-    if (a.pos_mode == kPosScan) {
-      px += 1;
-      if (px >= w) {
-        px = 0;
-        py += 1;
-        if (py >= h) py = 0;
-      }
-    } else {
-      uint64_t u = draw(er.key, 3, (uint32_t)er.t);
-      py = below((uint32_t)(u >> 32), h);
-      px = below((uint32_t)u, w);
-    }
-  }
 
   // ---- store
-  if (valid && L.y == 0) {
+  if (wm.primary && L.y == 0) {
     er.h = (uint8_t)h;
     er.w = (uint8_t)w;
-    er.py = (uint8_t)py;
-    er.px = (uint8_t)px;
-    a.env[env] = er;
-    if (changed || restart) store_metrics<S, PROBLEM>(a.metrics + (size_t)env * kMaxMetrics, mn);
-    if (a.reward) a.reward[env] = reward;
-    if (a.done) a.done[env] = done ? 1 : 0;
+    er.py = (uint8_t)qy;
+    er.px = (uint8_t)qx;
+    a.env[wm.env] = er;
+    if (changed || restart) store_metrics<S, PROBLEM>(a.metrics + (size_t)wm.env * kMaxMetrics, mn);
+    if (a.reward) a.reward[wm.env] = reward;
+    if (a.done) a.done[wm.env] = done ? 1 : 0;
   }
-
-  // ---- observation around the new position
-  if (a.obs != nullptr) write_obs<S, PROBLEM>(a, L, lds, p, inside, py, px, env0, nvalid);
+  if (a.obs != nullptr && any_restart) observe<S, PROBLEM>(a, L, wm, p, inside, qy, qx);
 }
 
 // ------------------------------------------------- plain-layout conversion
@@ -916,6 +1012,29 @@ __global__ __launch_bounds__(64) void selftest_kernel(int32_t* mismatches) {
     uint64_t up = __shfl_up(v64, 1), dn = __shfl_down(v64, 1);
     bad += L.from_above(v64) != (L.y == 0 ? 0ull : up);
     bad += L.from_below(v64) != (L.y == 63 ? 0ull : dn);
+  }
+  // group reductions against a plain shuffle butterfly
+  int iv = (int)(v32 >> 20) - 1000;
+  {
+    Lanes<16> L;
+    int sum = iv, mx = iv;
+    for (int o = 8; o > 0; o >>= 1) { sum += __shfl_xor(sum, o); mx = max(mx, __shfl_xor(mx, o)); }
+    bad += L.gsum(iv) != sum;
+    bad += L.gmax(iv) != mx;
+  }
+  {
+    Lanes<32> L;
+    int sum = iv, mx = iv;
+    for (int o = 16; o > 0; o >>= 1) { sum += __shfl_xor(sum, o); mx = max(mx, __shfl_xor(mx, o)); }
+    bad += L.gsum(iv) != sum;
+    bad += L.gmax(iv) != mx;
+  }
+  {
+    Lanes<64> L;
+    int sum = iv, mx = iv;
+    for (int o = 32; o > 0; o >>= 1) { sum += __shfl_xor(sum, o); mx = max(mx, __shfl_xor(mx, o)); }
+    bad += L.gsum(iv) != sum;
+    bad += L.gmax(iv) != mx;
   }
   if (bad) atomicAdd(mismatches, bad);
 }

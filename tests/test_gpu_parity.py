@@ -43,9 +43,14 @@ SMALL = [
 ]
 
 
+@pytest.mark.parametrize("lpw", [0, 2, 4], ids=["auto", "lpw2", "lpw4"])
 @pytest.mark.parametrize("label,cfg,steps,extra", SMALL, ids=[s[0] for s in SMALL])
-def test_small_configs_every_step(label, cfg, steps, extra):
-    run_parity(cfg, steps, label=label, **extra)
+def test_small_configs_every_step(label, cfg, steps, extra, lpw):
+    """lpw = levels packed into one wavefront: automatic (1 at these batch sizes), 2, and as many
+    as the size class takes."""
+    if lpw and max(cfg["max_h"], cfg["max_w"]) > 32:
+        pytest.skip("a 64-row level fills the wavefront")
+    run_parity(dict(cfg, levels_per_wave=lpw), steps, label=f"{label} lpw={lpw}", **extra)
 
 
 def test_control_targets_and_fractional_weights():
@@ -137,7 +142,7 @@ def test_results_do_not_depend_on_batch_partition():
 def test_argument_errors_are_reported_not_raised_by_the_gpu():
     bad = wl.workload("maze16", batch=4)
     for field, val in (("obs_w", 64), ("max_h", 65), ("batch", 0), ("problem", 3), ("n_frozen", 9),
-                       ("min_h", 17), ("max_steps", 0), ("pad_mode", 2)):
+                       ("min_h", 17), ("max_steps", 0), ("pad_mode", 2), ("levels_per_wave", 5)):
         with pytest.raises(binding.PcgrlError):
             binding.Pcgrl(dict(bad, **{field: val}), 0)
     env = binding.Pcgrl(bad, 0)
@@ -148,3 +153,52 @@ def test_argument_errors_are_reported_not_raised_by_the_gpu():
     assert env.L.pcgrl_step(env.h, None, None, None, None, None) == -1
     assert env.L.pcgrl_step(None, None, None, None, None, None) == -1
     env.close()
+
+
+def test_steps_captured_in_a_hip_graph_replay_like_eager_calls():
+    """pcgrl_step only launches a kernel, so a caller may capture it.  Replays (with eager work and
+    synchronisation between them, and an auto-reset falling inside the graph) must give what the
+    same calls give eagerly, and what the oracle gives."""
+    dev = torch.device("cuda", 0)
+    n, reps = 20, 4
+    cfg = wl.workload("maze16", batch=300, max_steps=35)
+    acts_np = wl.random_actions(cfg, 5, n)
+    acts = torch.from_numpy(acts_np).to(dev)
+    B = cfg["batch"]
+    eager, graphed, cpu = binding.Pcgrl(cfg, 0), binding.Pcgrl(cfg, 0), oracle.Oracle(cfg)
+    obs_e = eager.new_obs()
+    rew_e = torch.empty(B, dtype=torch.float32, device=dev)
+    done_e = torch.empty(B, dtype=torch.uint8, device=dev)
+    obs_g = torch.empty((n,) + graphed.obs_shape, dtype=torch.uint8, device=dev)
+    rew_g = torch.empty((n, B), dtype=torch.float32, device=dev)
+    done_g = torch.empty((n, B), dtype=torch.uint8, device=dev)
+    eager.pcgrl_reset(11, obs_e)
+    cpu.reset(11)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        graphed.pcgrl_reset(11)
+        with torch.cuda.graph(g, stream=side):
+            for t in range(n):
+                graphed.pcgrl_step(acts[t], obs_g[t], rew_g[t], done_g[t])
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graphed.pcgrl_reset(11)          # capture does not execute; start both from the same state
+    for rep in range(reps):
+        g.replay()
+        torch.cuda.synchronize()
+        for t in range(n):
+            eager.pcgrl_step(acts[t], obs_e, rew_e, done_e)
+            o, r, d = cpu.step(acts_np[t])
+            ctx = f"replay {rep} step {t}"
+            assert torch.equal(obs_g[t], obs_e), ctx
+            assert torch.equal(rew_g[t], rew_e) and torch.equal(done_g[t], done_e), ctx
+            assert_same("obs", obs_g[t], o, ctx)
+            assert np.array_equal(rew_g[t].cpu().numpy(), r) and np.array_equal(done_g[t].cpu().numpy(), d), ctx
+        assert torch.equal(graphed.pcgrl_metrics(), eager.pcgrl_metrics())
+        assert_same("metrics", graphed.pcgrl_metrics(), cpu.metrics(), f"replay {rep}")
+        compare_state(graphed, cpu, f"replay {rep}")
+        (obs_e.float().sum() + 1).item()      # unrelated eager work between replays
+    for e in (eager, graphed):
+        e.close()
