@@ -93,8 +93,8 @@ typedef struct {
                            2^32 (entry k = P(tile <= k)); the last tile takes the rest; all zero =
                            start from an all-empty map                      (Methods / Task) */
   float weights[PCGRL_MAX_METRICS];     /* reward weight of each metric      (Methods / Training) */
-  int32_t target_lo[PCGRL_MAX_METRICS]; /* default target range of each metric; the loss of a */
-  int32_t target_hi[PCGRL_MAX_METRICS]; /* metric v is max(0, lo - v, v - hi) */
+  int32_t target_lo[PCGRL_MAX_METRICS]; /* default target range of each metric (clamped to */
+  int32_t target_hi[PCGRL_MAX_METRICS]; /* 0..65535); the loss of a metric v is max(0, lo - v, v - hi) */
 } pcgrl_config;
 
 /* Fills *cfg with this library's defaults for a problem: fixed 16x16 map, window 31, border
@@ -104,7 +104,7 @@ typedef struct {
 int pcgrl_config_default(int32_t problem, pcgrl_config* cfg);
 
 /* Creates a context on GPU `device` and allocates all device state (about
- * 3*S*8 + 230 bytes per environment, S = 16, 32 or 64 covering max_h and max_w).  The
+ * 3*S*8 + 170 bytes per environment, S = 16, 32 or 64 covering max_h and max_w).  The
  * environments start as if pcgrl_reset(seed = 0) had been called.  Synchronises.
  * cfg, out: host pointers.  Errors: E_NULL, E_CONFIG, E_DEVICE, E_NOMEM, E_HIP. */
 int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device);
@@ -153,8 +153,9 @@ int pcgrl_set_state(pcgrl_ctx* ctx, const int8_t* tiles, const uint8_t* frozen, 
                     const int16_t* pos, void* stream);
 
 /* Per-environment target ranges (control targets of Methods / Training).
- * targets: device, int32 [batch][M][2] = (lo, hi).  They stay in force until the next
- * pcgrl_reset, which restores the configuration's defaults. */
+ * targets: device, int32 [batch][M][2] = (lo, hi), each clamped to 0..65535 (no metric of a
+ * 64x64 level exceeds 4096).  They stay in force until the next pcgrl_reset, which restores the
+ * configuration's defaults. */
 int pcgrl_set_targets(pcgrl_ctx* ctx, const int32_t* targets, void* stream);
 
 /* Shape queries (host side, no GPU work).  out: host pointer to 4 ints = batch, C, obs_w, obs_w. */

@@ -186,9 +186,9 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   ctx->C = ctx->K + (cfg->pad_mode == PCGRL_PAD_BORDER ? 1 : 0);
   // Levels per wavefront: all G groups when the batch alone fills the machine; fewer (the spare
   // groups then hold copies that share the observation work) when that is what it takes to have
-  // a few wavefronts on each of the 1024 SIMDs.
+  // about two wavefronts on each of the 1024 SIMDs (measured optimum).
   ctx->epw = ctx->G;
-  while (ctx->epw > 1 && (cfg->batch + ctx->epw - 1) / ctx->epw < 4096) ctx->epw /= 2;
+  while (ctx->epw > 1 && (cfg->batch + ctx->epw - 1) / ctx->epw < 2048) ctx->epw /= 2;
   if (cfg->levels_per_wave > 0) {  // explicit choice, rounded down to what the size class allows
     ctx->epw = 1;
     while (ctx->epw * 2 <= cfg->levels_per_wave && ctx->epw * 2 <= ctx->G) ctx->epw *= 2;
@@ -210,7 +210,7 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
       {&ctx->d_frozen, rows * ctx->word_bytes},
       {&ctx->d_env, (size_t)ctx->B_pad * sizeof(EnvRec)},
       {&ctx->d_metrics, (size_t)ctx->B_pad * kMaxMetrics * sizeof(int32_t)},
-      {&ctx->d_targets, (size_t)ctx->B_pad * kMaxMetrics * 2 * sizeof(int32_t)},
+      {&ctx->d_targets, (size_t)ctx->B_pad * kMaxMetrics * sizeof(uint32_t)},
       {&ctx->d_bad, sizeof(unsigned long long)},
   };
   for (auto& al : allocs) *al.p = nullptr;
@@ -229,7 +229,7 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   a.frozen = ctx->d_frozen;
   a.env = static_cast<EnvRec*>(ctx->d_env);
   a.metrics = static_cast<int32_t*>(ctx->d_metrics);
-  a.targets = static_cast<int32_t*>(ctx->d_targets);
+  a.targets = static_cast<uint32_t*>(ctx->d_targets);
   a.bad_actions = static_cast<unsigned long long*>(ctx->d_bad);
   a.B = cfg->batch;
   a.plane_stride = (int32_t)rows;
@@ -247,7 +247,8 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   a.regions_mode = cfg->regions_mode;
   a.env_obs_bytes = (int32_t)E;
   a.nwaves = ctx->nwaves;
-  a.envs_per_wave = ctx->epw;
+  a.envs_per_wave_log2 = ctx->epw == 4 ? 2 : ctx->epw == 2 ? 1 : 0;
+  a.use_frozen = cfg->n_frozen > 0 ? 1 : 0;
   // One step's observations are rewritten every step.  Up to a few hundred MB ordinary stores
   // are faster (the 256 MB last-level cache absorbs most of them and keeps them for the
   // consumer); well beyond it streaming stores reach HBM at a higher rate (measured: 504 MB per
@@ -346,15 +347,16 @@ int pcgrl_set_state(pcgrl_ctx* ctx, const int8_t* tiles, const uint8_t* frozen, 
     hipLaunchKernelGGL(set_state_kernel<uint32_t>, dim3((n + 255) / 256), dim3(256), 0, st, ctx->base,
                        ctx->S, ctx->P, ctx->K, tiles, frozen, hw, pos);
   if (hipGetLastError() != hipSuccess) return PCGRL_E_HIP;
+  if (frozen) ctx->base.use_frozen = 1;  // from now on steps have to look pinpoints up
   return launch_init(ctx, kInitMetrics, ctx->base.seed, nullptr, st);
 }
 
 int pcgrl_set_targets(pcgrl_ctx* ctx, const int32_t* targets, void* stream) {
   if (!ctx || !targets) return PCGRL_E_NULL;
   DeviceGuard guard(ctx->device);
-  const int n = ctx->cfg.batch * ctx->M * 2;
+  const int n = ctx->cfg.batch * ctx->M;
   hipLaunchKernelGGL(set_targets_kernel, dim3((n + 255) / 256), dim3(256), 0,
-                     static_cast<hipStream_t>(stream), targets, static_cast<int32_t*>(ctx->d_targets),
+                     static_cast<hipStream_t>(stream), targets, static_cast<uint32_t*>(ctx->d_targets),
                      ctx->cfg.batch, ctx->M);
   return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
 }

@@ -34,8 +34,9 @@ struct __attribute__((aligned(16))) EnvRec {
   int32_t t;
   int32_t n_changes;
   int32_t episode;
-  uint64_t key;  // generator key of (seed, env, episode)
-  uint64_t pad_;
+  uint64_t key;          // generator key of (seed, env, episode)
+  uint32_t cell_frozen;  // the agent's current cell is a pinpoint
+  uint32_t pad_;
 };
 static_assert(sizeof(EnvRec) == 32, "EnvRec must be 32 bytes");
 
@@ -44,7 +45,7 @@ struct KArgs {
   void* frozen;      // word [plane_stride]
   EnvRec* env;       // [B_pad]
   int32_t* metrics;  // [B_pad][16]
-  int32_t* targets;  // [B_pad][16][2]
+  uint32_t* targets; // [B_pad][16], lo | hi << 16 (ranges are clamped to 0..65535)
   const int32_t* actions;
   uint8_t* obs;
   float* reward;
@@ -56,8 +57,9 @@ struct KArgs {
   int32_t obs_w, pad_mode, pos_mode, n_frozen, max_steps, max_changes, autoreset, regions_mode;
   int32_t env_obs_bytes;  // C * obs_w * obs_w
   int32_t nwaves;         // wavefronts that have work
-  int32_t envs_per_wave;  // distinct levels per wavefront: a divisor of 64 / S
+  int32_t envs_per_wave_log2;  // distinct levels per wavefront = 1 << this; at most 64 / S
   int32_t stream_obs;     // non-zero: write observations with non-temporal stores
+  int32_t use_frozen;     // zero: no level of this context has a pinpoint cell
   int32_t lds_words;      // LDS words of one wavefront's staging area
   int32_t flags;          // init kernel only
   uint32_t cdf[8];
@@ -418,6 +420,10 @@ __device__ __forceinline__ void full_metrics(const Lanes<S>& L,
 }
 
 __device__ __forceinline__ int loss(int v, int lo, int hi) { return max(0, max(lo - v, v - hi)); }
+// a target range as it is kept on the device
+__device__ __forceinline__ uint32_t pack_range(int lo, int hi) {
+  return (uint32_t)min(max(lo, 0), 65535) | ((uint32_t)min(max(hi, 0), 65535) << 16);
+}
 
 // ---------------------------------------------------------------- episodes
 
@@ -524,16 +530,24 @@ __device__ __forceinline__ void write_obs(const KArgs& a, const Lanes<S>& L, con
       if constexpr (WIDE || S == 64) return (BW)(((uint64_t)row >> sr) << sl_) & owmask;
       else return (BW)((row >> sr) << sl_) & owmask;
     };
-    const BW out_win = (BW)~window(inside) & owmask;  // window cells outside the map's columns
+    // the lane's own row seen through the window: each code plane and the inside mask
+    BW wp[PR::P];
+#pragma unroll
+    for (int k = 0; k < PR::P; ++k) wp[k] = window(p[k]);
+    const BW win_in = window(inside);
+    const BW out_win = (BW)~win_in & owmask;  // window cells outside the map's columns
     const int padc = a.pad_mode == kPadBorder ? PR::K : 1;
     const int cstride = ow * ow;
     for (int i = (L.y - y0) & (S - 1); i < ow; i += S) {
       const bool real = (y0 + i) == L.y;  // otherwise the row lies above or below the buffer
+      const BW in_real = real ? win_in : (BW)0;     // cells of this window row that lie in the map
+      const BW pad_bits = real ? out_win : owmask;  // cells of this window row that lie outside
       int off = d + sl.slot * E + i * ow + sl.copy * cstride;
       for (int c = sl.copy; c < C; c += sl.copies, off += sl.copies * cstride) {
-        const BW in_map = c < PR::K ? window(channel_row<PROBLEM, W>(p, inside, c)) : (BW)0;
-        const BW pad_real = c == padc ? out_win : (BW)0, pad_all = c == padc ? owmask : (BW)0;
-        const BW bits = real ? (BW)(in_map | pad_real) : pad_all;
+        BW bits = c < PR::K ? in_real : (BW)0;
+#pragma unroll
+        for (int k = 0; k < PR::P; ++k) bits &= ((c >> k) & 1) ? wp[k] : (BW)~wp[k];
+        bits |= c == padc ? pad_bits : (BW)0;
         if (bits != 0) {
           const int w0 = off >> 5, sh = off & 31;
           if constexpr (WIDE) {
@@ -630,11 +644,12 @@ template <int S> struct WaveMap {
     wave = (int)blockIdx.x * (int)(blockDim.x >> 6) + wave_in_block;
     if (wave >= a.nwaves) return false;  // whole wavefronts leave; no block-wide barrier is used
     lds = lds_all + (size_t)wave_in_block * a.lds_words;
-    const int epw = G == 1 ? 1 : a.envs_per_wave;
-    sl.copies = G / epw;
-    sl.slot = G == 1 ? 0 : L.g % epw;
-    sl.copy = G == 1 ? 0 : L.g / epw;
-    env0 = wave * epw;
+    const int lg = G == 1 ? 0 : a.envs_per_wave_log2;  // levels per wavefront = 1 << lg
+    const int epw = 1 << lg;
+    sl.copies = G >> lg;
+    sl.slot = L.g & (epw - 1);
+    sl.copy = L.g >> lg;
+    env0 = wave << lg;
     nvalid = min(epw, a.B - env0);
     env = env0 + sl.slot;
     valid = env < a.B;
@@ -679,6 +694,7 @@ __global__ __launch_bounds__(kMaxBlock) void init_kernel(KArgs a) {
     er.episode = 0;
     er.pad_ = 0;
     begin_episode<S, PROBLEM>(a, L, er.key, p, fz, h, w, py, px);
+    er.cell_frozen = L.gany(L.y == py && ((fz >> px) & 1)) ? 1u : 0u;
     er.h = (uint8_t)h;
     er.w = (uint8_t)w;
     er.py = (uint8_t)py;
@@ -697,6 +713,11 @@ __global__ __launch_bounds__(kMaxBlock) void init_kernel(KArgs a) {
     px = er.px;
 #pragma unroll
     for (int i = 0; i < PR::P; ++i) p[i] = planes[(size_t)i * a.plane_stride + ridx];
+    if (a.flags & kInitMetrics) {  // a level was installed: its pinpoint flag has to be refreshed
+      fz = frozen[ridx];
+      er.cell_frozen = L.gany(L.y == py && ((fz >> px) & 1)) ? 1u : 0u;
+      if (wm.primary && L.y == 0) a.env[wm.env] = er;
+    }
   }
   const W inside = inside_row<W>(L.y, h, w);
   if (a.flags & kInitMetrics) {
@@ -704,10 +725,8 @@ __global__ __launch_bounds__(kMaxBlock) void init_kernel(KArgs a) {
     full_metrics<S, PROBLEM>(L, p, inside, wm.valid, m);
     if (wm.primary && L.y == 0) store_metrics<S, PROBLEM>(a.metrics + (size_t)wm.env * kMaxMetrics, m);
   }
-  if ((a.flags & kInitTargets) && wm.primary && L.y < PR::M) {
-    a.targets[((size_t)wm.env * kMaxMetrics + L.y) * 2 + 0] = a.target_lo[L.y];
-    a.targets[((size_t)wm.env * kMaxMetrics + L.y) * 2 + 1] = a.target_hi[L.y];
-  }
+  if ((a.flags & kInitTargets) && wm.primary && L.y < PR::M)
+    a.targets[(size_t)wm.env * kMaxMetrics + L.y] = pack_range(a.target_lo[L.y], a.target_hi[L.y]);
   if ((a.flags & kInitObs) && a.obs != nullptr) observe<S, PROBLEM>(a, L, wm, p, inside, py, px);
 }
 
@@ -729,18 +748,17 @@ __global__ __launch_bounds__(kMaxBlock) void step_kernel(KArgs a) {
   W p[PR::P];
 #pragma unroll
   for (int i = 0; i < PR::P; ++i) p[i] = planes[(size_t)i * a.plane_stride + ridx];
-  const W fz = frozen[ridx];
   EnvRec er = a.env[wm.envl];
   const int act = valid ? a.actions[wm.envl] : -1;
   int mo[PR::M];
   load_metrics<S, PROBLEM>(a.metrics + (size_t)wm.envl * kMaxMetrics, mo);
-  constexpr int kTg = (2 * PR::M + 3) / 4 * 4;
-  int tg[kTg];
+  constexpr int kTg = (PR::M + 3) / 4 * 4;
+  uint32_t tg[kTg];  // packed target ranges
   {
-    const int4* tv = reinterpret_cast<const int4*>(a.targets + (size_t)wm.envl * kMaxMetrics * 2);
+    const uint4* tv = reinterpret_cast<const uint4*>(a.targets + (size_t)wm.envl * kMaxMetrics);
 #pragma unroll
     for (int q = 0; q < kTg / 4; ++q) {
-      int4 t = tv[q];
+      uint4 t = tv[q];
       tg[4 * q + 0] = t.x;
       tg[4 * q + 1] = t.y;
       tg[4 * q + 2] = t.z;
@@ -757,7 +775,7 @@ __global__ __launch_bounds__(kMaxBlock) void step_kernel(KArgs a) {
   int old_code = 0;
 #pragma unroll
   for (int i = 0; i < PR::P; ++i) old_code |= (L.gany(at_row && ((p[i] >> px) & 1)) ? 1 : 0) << i;
-  const bool is_frozen = L.gany(at_row && ((fz >> px) & 1));
+  const bool is_frozen = er.cell_frozen != 0;
   const bool in_range = act >= 0 && act < PR::K;
   const bool changed = valid && in_range && !is_frozen && act != old_code;
   {
@@ -789,6 +807,9 @@ __global__ __launch_bounds__(kMaxBlock) void step_kernel(KArgs a) {
     qy = below((uint32_t)(u >> 32), h);
     qx = below((uint32_t)u, w);
   }
+  // pinpoint flag of the cell the next step will edit (one word, off the critical path)
+  W next_fz_row = 0;
+  if (a.use_frozen) next_fz_row = frozen[(size_t)wm.envl * S + qy];
   // ---- observation around the new position.  It is issued before the metrics so that its
   // stores drain while the floods run; a wavefront in which some level restarts writes it last,
   // from the new episode's level.
@@ -853,7 +874,8 @@ __global__ __launch_bounds__(kMaxBlock) void step_kernel(KArgs a) {
     if (changed) {
 #pragma unroll
       for (int i = 0; i < PR::M; ++i) {
-        int dl = loss(mo[i], tg[2 * i], tg[2 * i + 1]) - loss(mn[i], tg[2 * i], tg[2 * i + 1]);
+        const int lo = (int)(tg[i] & 0xffffu), hi = (int)(tg[i] >> 16);
+        int dl = loss(mo[i], lo, hi) - loss(mn[i], lo, hi);
         reward = __fadd_rn(reward, __fmul_rn(a.weights[i], (float)dl));
       }
     }
@@ -881,6 +903,7 @@ __global__ __launch_bounds__(kMaxBlock) void step_kernel(KArgs a) {
       w = nw;
       qy = npy;
       qx = npx;
+      next_fz_row = L.gread(nfz, npy);
       er.key = nkey;
       er.episode += 1;
       er.t = 0;
@@ -894,6 +917,7 @@ __global__ __launch_bounds__(kMaxBlock) void step_kernel(KArgs a) {
     er.w = (uint8_t)w;
     er.py = (uint8_t)qy;
     er.px = (uint8_t)qx;
+    er.cell_frozen = (uint32_t)((next_fz_row >> qx) & 1);
     a.env[wm.env] = er;
     if (changed || restart) store_metrics<S, PROBLEM>(a.metrics + (size_t)wm.env * kMaxMetrics, mn);
     if (a.reward) a.reward[wm.env] = reward;
@@ -982,11 +1006,11 @@ __global__ void copy_metrics_kernel(const int32_t* src, int32_t* dst, int B, int
   dst[idx] = src[(size_t)(idx / M) * kMaxMetrics + idx % M];
 }
 
-__global__ void set_targets_kernel(const int32_t* src, int32_t* dst, int B, int M) {
+__global__ void set_targets_kernel(const int32_t* src, uint32_t* dst, int B, int M) {
   int idx = (int)(blockIdx.x * blockDim.x + threadIdx.x);
-  if (idx >= B * M * 2) return;
-  int env = idx / (2 * M), r = idx % (2 * M);
-  dst[(size_t)env * kMaxMetrics * 2 + r] = src[idx];
+  if (idx >= B * M) return;
+  int env = idx / M, i = idx % M;
+  dst[(size_t)env * kMaxMetrics + i] = pack_range(src[2 * idx], src[2 * idx + 1]);
 }
 
 // Cross-lane exchange check: the DPP shifts against the plain shuffle definition.
