@@ -108,6 +108,7 @@ def main():
     ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
                     help="replay a HIP graph of pcgrl_step launches (default) or call it from Python")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    ap.add_argument("--no-rollout", action="store_true", help="skip the pcgrl_rollout leg")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run 20 plain device copies of MIB MiB (the known "
                          "traffic that scales rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
@@ -214,6 +215,39 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_from_profiles(tag),
                      "kernel": "step_kernel", "avg_launch_us": launch_s * 1e6},
     }
+    # The same K steps driven through pcgrl_rollout: T steps per launch, levels resident in
+    # registers in between, every step still writes its observation (into one slot, as the loop
+    # above does), reward and done flag.  Reported beside the headline, never instead of it.
+    if not args.no_rollout:
+        T = min(chunk, 100)
+        launches = max(1, K // T)
+        racts = acts[:T].contiguous()
+        robs = obs.unsqueeze(0)
+        rrew = torch.empty((T, B), dtype=torch.float32, device=dev)
+        rdone = torch.empty((T, B), dtype=torch.uint8, device=dev)
+        env.pcgrl_reset(seed, obs)
+        env.pcgrl_rollout(racts, robs, rrew, rdone)
+        r0 = torch.cuda.Event(enable_timing=True)
+        r1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        r0.record()
+        for _ in range(launches):
+            env.pcgrl_rollout(racts, robs, rrew, rdone)
+        r1.record()
+        torch.cuda.synchronize()
+        rwall = time.perf_counter() - t0
+        rbytes = wl.obs_bytes(cfg) + 4 + 4 + 1          # per env-step: obs + action + reward + done
+        rlaunch_s = r0.elapsed_time(r1) * 1e-3 / launches
+        out["rollout"] = {
+            "value": B * T * launches / rwall, "unit": "env-steps/s", "steps_per_launch": T,
+            "launches": launches, "us_per_step": rwall / (T * launches) * 1e6,
+            "algorithmic_bytes_per_env_step": rbytes,
+            "roofline": {"bound": "hbm", "achieved": rbytes * B * T / rlaunch_s / 1e9,
+                         "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": rbytes * B * T / rlaunch_s / 1e9 / HBM_PEAK_GBS,
+                         "kernel": "step_kernel<..., rollout>", "avg_launch_us": rlaunch_s * 1e6},
+        }
     env.close()
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(cfg, seed, aseed)

@@ -131,6 +131,19 @@ int pcgrl_reset(pcgrl_ctx* ctx, uint64_t seed, uint8_t* obs, void* stream);
 int pcgrl_step(pcgrl_ctx* ctx, const int32_t* actions, uint8_t* obs, float* reward, uint8_t* done,
                void* stream);
 
+/* n_steps consecutive environment steps in ONE launch, with results identical to n_steps calls of
+ * pcgrl_step; the levels stay in registers in between, so per step only the action is read and
+ * the outputs are written (the random-agent rollout of Results / Speed comparison, and the remedy
+ * for batches too small to hide a launch per step).
+ *   actions: device, int32 [n_steps][batch]
+ *   obs    : device, uint8 [obs_slots][batch][C][obs_w][obs_w]; step t writes slot t % obs_slots
+ *            (obs_slots = n_steps keeps every observation, 1 keeps only the last).  May be NULL.
+ *   reward : device, float32 [n_steps][batch], may be NULL
+ *   done   : device, uint8 [n_steps][batch], may be NULL
+ * Errors: E_NULL; E_CONFIG if n_steps < 1 or obs_slots is not in 1..n_steps. */
+int pcgrl_rollout(pcgrl_ctx* ctx, const int32_t* actions, int32_t n_steps, uint8_t* obs,
+                  int32_t obs_slots, float* reward, uint8_t* done, void* stream);
+
 /* Copies the cached metric vectors.  out: device, int32 [batch][M]. */
 int pcgrl_metrics(pcgrl_ctx* ctx, int32_t* out, void* stream);
 

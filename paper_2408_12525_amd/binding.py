@@ -33,7 +33,7 @@ class PcgrlConfig(C.Structure):
 
 
 EXPORTS = [
-    "pcgrl_config_default", "pcgrl_create", "pcgrl_destroy", "pcgrl_reset", "pcgrl_step",
+    "pcgrl_config_default", "pcgrl_create", "pcgrl_destroy", "pcgrl_reset", "pcgrl_step", "pcgrl_rollout",
     "pcgrl_metrics", "pcgrl_observe", "pcgrl_get_state", "pcgrl_set_state", "pcgrl_set_targets",
     "pcgrl_obs_shape", "pcgrl_num_metrics", "pcgrl_num_tiles", "pcgrl_bad_action_count",
     "pcgrl_selftest", "pcgrl_strerror",
@@ -66,6 +66,7 @@ def load():
     L.pcgrl_destroy.argtypes = [p]
     L.pcgrl_reset.argtypes = [p, u64, p, p]
     L.pcgrl_step.argtypes = [p, p, p, p, p, p]
+    L.pcgrl_rollout.argtypes = [p, p, i32, p, i32, p, p, p]
     L.pcgrl_metrics.argtypes = [p, p, p]
     L.pcgrl_observe.argtypes = [p, p, p]
     L.pcgrl_get_state.argtypes = [p, p, p, p, p, p, p]
@@ -173,6 +174,21 @@ class Pcgrl:
         r = self._dev(reward, torch.float32, (self.B,), "reward", optional=True)
         d = self._dev(done, torch.uint8, (self.B,), "done", optional=True)
         _check(self.L.pcgrl_step(self.h, a, o, r, d, self._st()), "pcgrl_step")
+
+    def pcgrl_rollout(self, actions, obs=None, reward=None, done=None):
+        """actions [T, B]; obs [slots, B, C, ow, ow] (slots <= T); reward / done [T, B]."""
+        if not isinstance(actions, torch.Tensor) or actions.dim() != 2:
+            raise PcgrlError("actions must be a [T, batch] tensor")
+        T = actions.shape[0]
+        a = self._dev(actions, torch.int32, (T, self.B), "actions")
+        slots = 1
+        o = None
+        if obs is not None:
+            slots = obs.shape[0] if obs.dim() == 5 else 0
+            o = self._dev(obs, torch.uint8, (slots,) + tuple(self.obs_shape), "obs")
+        r = self._dev(reward, torch.float32, (T, self.B), "reward", optional=True)
+        d = self._dev(done, torch.uint8, (T, self.B), "done", optional=True)
+        _check(self.L.pcgrl_rollout(self.h, a, T, o, slots, r, d, self._st()), "pcgrl_rollout")
 
     def pcgrl_metrics(self, out=None):
         if out is None:

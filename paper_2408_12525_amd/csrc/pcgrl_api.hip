@@ -76,7 +76,14 @@ int dispatch(int S, int problem, A&&... args) {
 
 template <int S, int PROBLEM> struct LaunchStep {
   static int run(const pcgrl_ctx* ctx, const KArgs& a, hipStream_t st) {
-    hipLaunchKernelGGL((step_kernel<S, PROBLEM>), dim3((ctx->nwaves + ctx->wpb - 1) / ctx->wpb),
+    hipLaunchKernelGGL((step_kernel<S, PROBLEM, false>), dim3((ctx->nwaves + ctx->wpb - 1) / ctx->wpb),
+                       dim3(64 * ctx->wpb), ctx->lds_bytes * ctx->wpb, st, a);
+    return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
+  }
+};
+template <int S, int PROBLEM> struct LaunchRollout {
+  static int run(const pcgrl_ctx* ctx, const KArgs& a, hipStream_t st) {
+    hipLaunchKernelGGL((step_kernel<S, PROBLEM, true>), dim3((ctx->nwaves + ctx->wpb - 1) / ctx->wpb),
                        dim3(64 * ctx->wpb), ctx->lds_bytes * ctx->wpb, st, a);
     return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
   }
@@ -301,6 +308,22 @@ int pcgrl_step(pcgrl_ctx* ctx, const int32_t* actions, uint8_t* obs, float* rewa
   a.reward = reward;
   a.done = done;
   return dispatch<LaunchStep>(ctx->S, ctx->cfg.problem, ctx, a, static_cast<hipStream_t>(stream));
+}
+
+int pcgrl_rollout(pcgrl_ctx* ctx, const int32_t* actions, int32_t n_steps, uint8_t* obs,
+                  int32_t obs_slots, float* reward, uint8_t* done, void* stream) {
+  if (!ctx || !actions) return PCGRL_E_NULL;
+  if (n_steps < 1 || n_steps > (1 << 20)) return PCGRL_E_CONFIG;
+  if (obs && (obs_slots < 1 || obs_slots > n_steps)) return PCGRL_E_CONFIG;
+  DeviceGuard guard(ctx->device);
+  KArgs a = ctx->base;
+  a.actions = actions;
+  a.obs = obs;
+  a.reward = reward;
+  a.done = done;
+  a.rollout_steps = n_steps;
+  a.obs_slots = obs ? obs_slots : 1;
+  return dispatch<LaunchRollout>(ctx->S, ctx->cfg.problem, ctx, a, static_cast<hipStream_t>(stream));
 }
 
 int pcgrl_metrics(pcgrl_ctx* ctx, int32_t* out, void* stream) {

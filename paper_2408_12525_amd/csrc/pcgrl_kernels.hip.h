@@ -62,6 +62,8 @@ struct KArgs {
   int32_t use_frozen;     // zero: no level of this context has a pinpoint cell
   int32_t lds_words;      // LDS words of one wavefront's staging area
   int32_t flags;          // init kernel only
+  int32_t rollout_steps;  // rollout kernel: steps per launch
+  int32_t obs_slots;      // rollout kernel: step t writes observation slot t % obs_slots
   uint32_t cdf[8];
   float weights[kMaxMetrics];
   int32_t target_lo[kMaxMetrics], target_hi[kMaxMetrics];
@@ -505,7 +507,7 @@ struct Slot {
 // widens 16 bits to 16 bytes and issues one aligned 16-byte store.  WIDE = window wider than 32.
 template <int S, int PROBLEM, bool WIDE>
 __device__ __forceinline__ void write_obs(const KArgs& a, const Lanes<S>& L, const Slot& sl,
-                                          uint32_t* lds,
+                                          uint32_t* lds, uint8_t* obs,
                                           const typename RowWord<S>::T (&p)[Prob<PROBLEM>::P],
                                           typename RowWord<S>::T inside, int qy, int qx, int env0,
                                           int nvalid) {
@@ -515,7 +517,7 @@ __device__ __forceinline__ void write_obs(const KArgs& a, const Lanes<S>& L, con
   const int ow = a.obs_w, r = ow >> 1;
   const int C = PR::K + (a.pad_mode == kPadBorder ? 1 : 0);
   const int E = a.env_obs_bytes;
-  uint8_t* region = a.obs + (size_t)env0 * (size_t)E;
+  uint8_t* region = obs + (size_t)env0 * (size_t)E;
   const int d = (int)((uintptr_t)region & 15u);
   const int total = d + nvalid * E;  // stream length in bits
   const int nwords = (total + 31) >> 5;
@@ -661,12 +663,13 @@ template <int S> struct WaveMap {
 
 template <int S, int PROBLEM>
 __device__ __forceinline__ void observe(const KArgs& a, const Lanes<S>& L, const WaveMap<S>& wm,
+                                        uint8_t* obs,
                                         const typename RowWord<S>::T (&p)[Prob<PROBLEM>::P],
                                         typename RowWord<S>::T inside, int qy, int qx) {
   if (a.obs_w > 32)
-    write_obs<S, PROBLEM, true>(a, L, wm.sl, wm.lds, p, inside, qy, qx, wm.env0, wm.nvalid);
+    write_obs<S, PROBLEM, true>(a, L, wm.sl, wm.lds, obs, p, inside, qy, qx, wm.env0, wm.nvalid);
   else
-    write_obs<S, PROBLEM, false>(a, L, wm.sl, wm.lds, p, inside, qy, qx, wm.env0, wm.nvalid);
+    write_obs<S, PROBLEM, false>(a, L, wm.sl, wm.lds, obs, p, inside, qy, qx, wm.env0, wm.nvalid);
 }
 
 // Reset / refresh / observe: flags choose between generating a fresh episode 0 from the seed or
@@ -727,11 +730,13 @@ __global__ __launch_bounds__(kMaxBlock) void init_kernel(KArgs a) {
   }
   if ((a.flags & kInitTargets) && wm.primary && L.y < PR::M)
     a.targets[(size_t)wm.env * kMaxMetrics + L.y] = pack_range(a.target_lo[L.y], a.target_hi[L.y]);
-  if ((a.flags & kInitObs) && a.obs != nullptr) observe<S, PROBLEM>(a, L, wm, p, inside, py, px);
+  if ((a.flags & kInitObs) && a.obs != nullptr) observe<S, PROBLEM>(a, L, wm, a.obs, p, inside, py, px);
 }
 
-// One environment step of every level (see pcgrl_step in the public header).
-template <int S, int PROBLEM>
+// One environment step of every level (pcgrl_step), or, with ROLL, `rollout_steps` consecutive
+// steps (pcgrl_rollout) during which the levels never leave the registers: per step only the
+// action is read and the observation, reward and done flag are written.
+template <int S, int PROBLEM, bool ROLL>
 __global__ __launch_bounds__(kMaxBlock) void step_kernel(KArgs a) {
   using W = typename RowWord<S>::T;
   using PR = Prob<PROBLEM>;
@@ -748,8 +753,10 @@ __global__ __launch_bounds__(kMaxBlock) void step_kernel(KArgs a) {
   W p[PR::P];
 #pragma unroll
   for (int i = 0; i < PR::P; ++i) p[i] = planes[(size_t)i * a.plane_stride + ridx];
+  W fz = 0;  // pinpoint rows: resident only in a rollout; a single step keeps a flag with the cell
+  if constexpr (ROLL) fz = frozen[ridx];
   EnvRec er = a.env[wm.envl];
-  const int act = valid ? a.actions[wm.envl] : -1;
+  int act = valid ? a.actions[wm.envl] : -1;
   int mo[PR::M];
   load_metrics<S, PROBLEM>(a.metrics + (size_t)wm.envl * kMaxMetrics, mo);
   constexpr int kTg = (PR::M + 3) / 4 * 4;
@@ -769,161 +776,214 @@ __global__ __launch_bounds__(kMaxBlock) void step_kernel(KArgs a) {
   for (int i = 0; i < kTg; ++i) asm volatile("" : "+v"(tg[i]));  // issue these loads here, not at their use
   int h = er.h, w = er.w, py = er.py, px = er.px;
   W inside = inside_row<W>(L.y, h, w);
-
-  // ---- edit (Methods / Training: the agent may change the tile it stands on)
-  const bool at_row = L.y == py;
-  int old_code = 0;
-#pragma unroll
-  for (int i = 0; i < PR::P; ++i) old_code |= (L.gany(at_row && ((p[i] >> px) & 1)) ? 1 : 0) << i;
-  const bool is_frozen = er.cell_frozen != 0;
-  const bool in_range = act >= 0 && act < PR::K;
-  const bool changed = valid && in_range && !is_frozen && act != old_code;
-  {
-    const uint64_t bad = __builtin_amdgcn_ballot_w64(wm.primary && !in_range && L.y == 0);
-    if (bad != 0 && L.lane == 0) atomicAdd(a.bad_actions, (unsigned long long)__popcll(bad));
-  }
-  if (changed && at_row) {
-#pragma unroll
-    for (int i = 0; i < PR::P; ++i) {
-      p[i] = (p[i] & ~((W)1 << px)) | ((W)((act >> i) & 1) << px);
-      if (wm.primary) planes[(size_t)i * a.plane_stride + ridx] = p[i];
-    }
-  }
-  // ---- counters, done flag and the agent's next cell need nothing but the edit
-  er.t += 1;
-  er.n_changes += changed ? 1 : 0;
-  const bool done = (er.t >= a.max_steps) || (a.max_changes > 0 && er.n_changes >= a.max_changes);
-  const bool restart = valid && done && a.autoreset != 0;
-  int qy = py, qx = px;
-  if (a.pos_mode == kPosScan) {
-    qx += 1;
-    if (qx >= w) {
-      qx = 0;
-      qy += 1;
-      if (qy >= h) qy = 0;
-    }
-  } else {
-    uint64_t u = draw(er.key, 3, (uint32_t)er.t);
-    qy = below((uint32_t)(u >> 32), h);
-    qx = below((uint32_t)u, w);
-  }
-  // pinpoint flag of the cell the next step will edit (one word, off the critical path)
+  bool planes_dirty = false, fz_dirty = false;  // ROLL: what has to be written back at the end
+  bool metrics_dirty = false;
   W next_fz_row = 0;
-  if (a.use_frozen) next_fz_row = frozen[(size_t)wm.envl * S + qy];
-  // ---- observation around the new position.  It is issued before the metrics so that its
-  // stores drain while the floods run; a wavefront in which some level restarts writes it last,
-  // from the new episode's level.
-  const bool any_restart = wave_any<S>(restart);
-  if (a.obs != nullptr && !any_restart) observe<S, PROBLEM>(a, L, wm, p, inside, qy, qx);
 
-  // ---- metrics, only where the edit modified the map (Methods / Task)
-  int mn[PR::M];
-#pragma unroll
-  for (int i = 0; i < PR::M; ++i) mn[i] = mo[i];
-  float reward = 0.0f;
-  if (wave_any<S>(changed)) {
-    const W in = changed ? inside : (W)0;  // unchanged levels look empty: their loops end at once
-    const W wall = channel_row<PROBLEM, W>(p, in, 1);
-    const W pass = in & ~wall;
-    // tile counts: one cell moved from one tile type to another
-#pragma unroll
-    for (int k = 0; k < PR::K; ++k)
-      mn[PR::CNT + k] += (changed && act == k ? 1 : 0) - (changed && old_code == k ? 1 : 0);
-    const bool was_pass = old_code != 1, now_pass = act != 1;
-    // regions
-    if (a.regions_mode == kRegionsRecount) {
-      int rc = regions_full<S>(L, pass);
-      if (changed) mn[0] = rc;
-    } else {
-      const bool flip = changed && was_pass != now_pass;
-      if (wave_any<S>(flip)) {
-        W cell = (flip && at_row) ? (W)1 << px : (W)0;
-        W passw = flip ? (pass & ~cell) : (W)0;
-        W nbr = (L.dilate(cell) & ~cell) & passw;
-        int k = neighbour_components<S>(L, nbr, passw);
-        if (flip) mn[0] = mo[0] + (now_pass ? 1 - k : k - 1);
-      }
+  const int nsteps = ROLL ? a.rollout_steps : 1;
+  for (int step = 0; step < nsteps; ++step) {
+    // the next step's action is requested now and used one iteration later
+    int act_next = -1;
+    if constexpr (ROLL) {
+      if (step + 1 < nsteps && valid) act_next = a.actions[(size_t)(step + 1) * a.B + wm.envl];
     }
-    // paths
-    if constexpr (PROBLEM == kBinary) {
-      int dm = two_sweep_diameter<S>(L, pass);
-      if (changed) mn[1] = dm;
-    } else if constexpr (PROBLEM == kMaze) {
-      W r;
-      int dd = nearest<S>(L, channel_row<PROBLEM, W>(p, in, 2), channel_row<PROBLEM, W>(p, in, 3), pass, r);
-      if (changed) mn[1] = dd < 0 ? 0 : dd;
+    uint8_t* obs = a.obs;
+    if constexpr (ROLL) {
+      if (obs != nullptr) obs += (size_t)(step % a.obs_slots) * (size_t)a.B * (size_t)a.env_obs_bytes;
+    }
+
+    // ---- edit (Methods / Training: the agent may change the tile it stands on)
+    const bool at_row = L.y == py;
+    int old_code = 0;
+#pragma unroll
+    for (int i = 0; i < PR::P; ++i) old_code |= (L.gany(at_row && ((p[i] >> px) & 1)) ? 1 : 0) << i;
+    bool is_frozen;
+    if constexpr (ROLL) is_frozen = L.gany(at_row && ((fz >> px) & 1));
+    else is_frozen = er.cell_frozen != 0;
+    const bool in_range = act >= 0 && act < PR::K;
+    const bool changed = valid && in_range && !is_frozen && act != old_code;
+    {
+      const uint64_t bad = __builtin_amdgcn_ballot_w64(wm.primary && !in_range && L.y == 0);
+      if (bad != 0 && L.lane == 0) atomicAdd(a.bad_actions, (unsigned long long)__popcll(bad));
+    }
+    if (changed && at_row) {
+#pragma unroll
+      for (int i = 0; i < PR::P; ++i) {
+        p[i] = (p[i] & ~((W)1 << px)) | ((W)((act >> i) & 1) << px);
+        if constexpr (!ROLL) {
+          if (wm.primary) planes[(size_t)i * a.plane_stride + ridx] = p[i];
+        }
+      }
+      planes_dirty = true;
+    }
+    metrics_dirty = metrics_dirty || changed;
+    // ---- counters, done flag and the agent's next cell need nothing but the edit
+    er.t += 1;
+    er.n_changes += changed ? 1 : 0;
+    const bool done = (er.t >= a.max_steps) || (a.max_changes > 0 && er.n_changes >= a.max_changes);
+    const bool restart = valid && done && a.autoreset != 0;
+    int qy = py, qx = px;
+    if (a.pos_mode == kPosScan) {
+      qx += 1;
+      if (qx >= w) {
+        qx = 0;
+        qy += 1;
+        if (qy >= h) qy = 0;
+      }
     } else {
-      // swapping empty and chest changes neither the graph nor any source or target set
-      const bool plain = (old_code == 0 || old_code == 6) && (act == 0 || act == 6);
-      const bool need = changed && !plain;
-      if (wave_any<S>(need)) {
-        const W inn = need ? in : (W)0;
-        const W passn = need ? pass : (W)0;
-        W k1, r;
-        int d1, de;
-        nearest_two<S>(L, channel_row<PROBLEM, W>(p, inn, 2), channel_row<PROBLEM, W>(p, inn, 3),
-                       channel_row<PROBLEM, W>(p, inn, 5), passn, d1, k1, de);
-        int d2 = nearest<S>(L, k1, channel_row<PROBLEM, W>(p, inn, 4), passn, r);
-        if (need) {
-          mn[1] = (d1 >= 0 && d2 >= 0) ? d1 + d2 : 0;
-          mn[2] = de < 0 ? 0 : de;
+      uint64_t u = draw(er.key, 3, (uint32_t)er.t);
+      qy = below((uint32_t)(u >> 32), h);
+      qx = below((uint32_t)u, w);
+    }
+    // pinpoint flag of the cell the next step will edit (one word, off the critical path)
+    if constexpr (!ROLL) {
+      if (a.use_frozen) next_fz_row = frozen[(size_t)wm.envl * S + qy];
+    }
+    // ---- observation around the new position.  It is issued before the metrics so that its
+    // stores drain while the floods run; a wavefront in which some level restarts writes it
+    // last, from the new episode's level.
+    const bool any_restart = wave_any<S>(restart);
+    if (obs != nullptr && !any_restart) observe<S, PROBLEM>(a, L, wm, obs, p, inside, qy, qx);
+
+    // ---- metrics, only where the edit modified the map (Methods / Task)
+    int mn[PR::M];
+#pragma unroll
+    for (int i = 0; i < PR::M; ++i) mn[i] = mo[i];
+    float reward = 0.0f;
+    if (wave_any<S>(changed)) {
+      const W in = changed ? inside : (W)0;  // unchanged levels look empty: their loops end at once
+      const W wall = channel_row<PROBLEM, W>(p, in, 1);
+      const W pass = in & ~wall;
+      // tile counts: one cell moved from one tile type to another
+#pragma unroll
+      for (int k = 0; k < PR::K; ++k)
+        mn[PR::CNT + k] += (changed && act == k ? 1 : 0) - (changed && old_code == k ? 1 : 0);
+      const bool was_pass = old_code != 1, now_pass = act != 1;
+      // regions
+      if (a.regions_mode == kRegionsRecount) {
+        int rc = regions_full<S>(L, pass);
+        if (changed) mn[0] = rc;
+      } else {
+        const bool flip = changed && was_pass != now_pass;
+        if (wave_any<S>(flip)) {
+          W cell = (flip && at_row) ? (W)1 << px : (W)0;
+          W passw = flip ? (pass & ~cell) : (W)0;
+          W nbr = (L.dilate(cell) & ~cell) & passw;
+          int k = neighbour_components<S>(L, nbr, passw);
+          if (flip) mn[0] = mo[0] + (now_pass ? 1 - k : k - 1);
+        }
+      }
+      // paths
+      if constexpr (PROBLEM == kBinary) {
+        int dm = two_sweep_diameter<S>(L, pass);
+        if (changed) mn[1] = dm;
+      } else if constexpr (PROBLEM == kMaze) {
+        W r;
+        int dd = nearest<S>(L, channel_row<PROBLEM, W>(p, in, 2), channel_row<PROBLEM, W>(p, in, 3), pass, r);
+        if (changed) mn[1] = dd < 0 ? 0 : dd;
+      } else {
+        // swapping empty and chest changes neither the graph nor any source or target set
+        const bool plain = (old_code == 0 || old_code == 6) && (act == 0 || act == 6);
+        const bool need = changed && !plain;
+        if (wave_any<S>(need)) {
+          const W inn = need ? in : (W)0;
+          const W passn = need ? pass : (W)0;
+          W k1, r;
+          int d1, de;
+          nearest_two<S>(L, channel_row<PROBLEM, W>(p, inn, 2), channel_row<PROBLEM, W>(p, inn, 3),
+                         channel_row<PROBLEM, W>(p, inn, 5), passn, d1, k1, de);
+          int d2 = nearest<S>(L, k1, channel_row<PROBLEM, W>(p, inn, 4), passn, r);
+          if (need) {
+            mn[1] = (d1 >= 0 && d2 >= 0) ? d1 + d2 : 0;
+            mn[2] = de < 0 ? 0 : de;
+          }
+        }
+      }
+      // reward = sum over metrics, in index order, of weight * (old loss - new loss)
+      if (changed) {
+#pragma unroll
+        for (int i = 0; i < PR::M; ++i) {
+          const int lo = (int)(tg[i] & 0xffffu), hi = (int)(tg[i] >> 16);
+          int dl = loss(mo[i], lo, hi) - loss(mn[i], lo, hi);
+          reward = __fadd_rn(reward, __fmul_rn(a.weights[i], (float)dl));
         }
       }
     }
-    // reward = sum over metrics, in index order, of weight * (old loss - new loss)
-    if (changed) {
+    // ---- auto-reset: fresh seeded episode for the finished levels; the others keep their registers
+    if (any_restart) {
+      W np[PR::P], nfz;
+      int nh, nw, npy, npx;
+      uint64_t nkey = env_key(a.seed, (uint64_t)wm.envl, (uint64_t)(er.episode + 1));
+      begin_episode<S, PROBLEM>(a, L, nkey, np, nfz, nh, nw, npy, npx);
+      W ninside = inside_row<W>(L.y, nh, nw);
+      int nm[PR::M];
+      full_metrics<S, PROBLEM>(L, np, ninside, restart, nm);
+      if (restart) {
 #pragma unroll
-      for (int i = 0; i < PR::M; ++i) {
-        const int lo = (int)(tg[i] & 0xffffu), hi = (int)(tg[i] >> 16);
-        int dl = loss(mo[i], lo, hi) - loss(mn[i], lo, hi);
-        reward = __fadd_rn(reward, __fmul_rn(a.weights[i], (float)dl));
+        for (int i = 0; i < PR::P; ++i) {
+          p[i] = np[i];
+          if constexpr (!ROLL) {
+            if (wm.primary) planes[(size_t)i * a.plane_stride + ridx] = np[i];
+          }
+        }
+        if constexpr (ROLL) {
+          fz = nfz;
+        } else {
+          if (wm.primary) frozen[ridx] = nfz;
+          next_fz_row = L.gread(nfz, npy);
+        }
+        planes_dirty = true;
+        fz_dirty = true;
+        metrics_dirty = true;
+#pragma unroll
+        for (int i = 0; i < PR::M; ++i) mn[i] = nm[i];
+        inside = ninside;
+        h = nh;
+        w = nw;
+        qy = npy;
+        qx = npx;
+        er.key = nkey;
+        er.episode += 1;
+        er.t = 0;
+        er.n_changes = 0;
       }
     }
-  }
-  // ---- auto-reset: fresh seeded episode for the finished levels; the others keep their registers
-  if (any_restart) {
-    W np[PR::P], nfz;
-    int nh, nw, npy, npx;
-    uint64_t nkey = env_key(a.seed, (uint64_t)wm.envl, (uint64_t)(er.episode + 1));
-    begin_episode<S, PROBLEM>(a, L, nkey, np, nfz, nh, nw, npy, npx);
-    W ninside = inside_row<W>(L.y, nh, nw);
-    int nm[PR::M];
-    full_metrics<S, PROBLEM>(L, np, ninside, restart, nm);
-    if (restart) {
-#pragma unroll
-      for (int i = 0; i < PR::P; ++i) {
-        p[i] = np[i];
-        if (wm.primary) planes[(size_t)i * a.plane_stride + ridx] = np[i];
-      }
-      if (wm.primary) frozen[ridx] = nfz;
-#pragma unroll
-      for (int i = 0; i < PR::M; ++i) mn[i] = nm[i];
-      inside = ninside;
-      h = nh;
-      w = nw;
-      qy = npy;
-      qx = npx;
-      next_fz_row = L.gread(nfz, npy);
-      er.key = nkey;
-      er.episode += 1;
-      er.t = 0;
-      er.n_changes = 0;
+
+    // ---- per-step outputs
+    if (wm.primary && L.y == 0) {
+      if (a.reward) a.reward[(size_t)step * a.B + wm.env] = reward;
+      if (a.done) a.done[(size_t)step * a.B + wm.env] = done ? 1 : 0;
     }
+    if (obs != nullptr && any_restart) observe<S, PROBLEM>(a, L, wm, obs, p, inside, qy, qx);
+
+    // ---- the new state becomes the current one
+    py = qy;
+    px = qx;
+#pragma unroll
+    for (int i = 0; i < PR::M; ++i) mo[i] = mn[i];
+    act = act_next;
   }
 
-  // ---- store
+  // ---- store the level's scalars (and, after a rollout, everything that changed)
+  if constexpr (ROLL) {
+    if (wm.primary) {
+      if (planes_dirty) {
+#pragma unroll
+        for (int i = 0; i < PR::P; ++i) planes[(size_t)i * a.plane_stride + ridx] = p[i];
+      }
+      if (fz_dirty) frozen[ridx] = fz;
+    }
+    next_fz_row = L.gread(fz, py);
+  }
   if (wm.primary && L.y == 0) {
     er.h = (uint8_t)h;
     er.w = (uint8_t)w;
-    er.py = (uint8_t)qy;
-    er.px = (uint8_t)qx;
-    er.cell_frozen = (uint32_t)((next_fz_row >> qx) & 1);
+    er.py = (uint8_t)py;
+    er.px = (uint8_t)px;
+    er.cell_frozen = (uint32_t)((next_fz_row >> px) & 1);
     a.env[wm.env] = er;
-    if (changed || restart) store_metrics<S, PROBLEM>(a.metrics + (size_t)wm.env * kMaxMetrics, mn);
-    if (a.reward) a.reward[wm.env] = reward;
-    if (a.done) a.done[wm.env] = done ? 1 : 0;
+    if (metrics_dirty) store_metrics<S, PROBLEM>(a.metrics + (size_t)wm.env * kMaxMetrics, mo);
   }
-  if (a.obs != nullptr && any_restart) observe<S, PROBLEM>(a, L, wm, p, inside, qy, qx);
 }
 
 // ------------------------------------------------- plain-layout conversion

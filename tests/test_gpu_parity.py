@@ -202,3 +202,79 @@ def test_steps_captured_in_a_hip_graph_replay_like_eager_calls():
         (obs_e.float().sum() + 1).item()      # unrelated eager work between replays
     for e in (eager, graphed):
         e.close()
+
+
+ROLLOUTS = [
+    ("binary16", wl.workload("binary16", batch=37, max_steps=23), 60, 60),
+    ("maze16 ring of 7 obs slots", wl.workload("maze16", batch=70, max_steps=31), 50, 7),
+    ("maze16 lpw4 pinpoints scan", wl.make_config(wl.MAZE, 50, 16, 9, n_frozen=4, max_steps=29, pos_mode=wl.POS_SCAN,
+                                                  levels_per_wave=4, probs=[.45, .45, .05, .05]), 64, 64),
+    ("binary32 rand ow15 pinpoints", wl.workload("binary32_rand_ow15", batch=33, max_steps=20), 45, 45),
+    ("dungeon32 lpw2", wl.workload("dungeon32", batch=21, max_steps=26, levels_per_wave=2), 40, 1),
+    ("maze64", wl.workload("maze64", batch=9, max_steps=17), 40, 40),
+    ("binary64 budget", wl.make_config(wl.BINARY, 5, 64, 63, min_size=40, n_frozen=5, max_changes=9, max_steps=100), 60, 3),
+]
+
+
+@pytest.mark.parametrize("label,cfg,T,slots", ROLLOUTS, ids=[r[0] for r in ROLLOUTS])
+def test_rollout_equals_the_same_steps_one_by_one(label, cfg, T, slots):
+    """pcgrl_rollout against the oracle stepped T times (every observation slot that survives,
+    every reward and done flag, final state and metrics), with auto-resets inside the rollout, and
+    against T calls of pcgrl_step."""
+    print(f"[rollout] {label} T={T} slots={slots}", flush=True)
+    dev = torch.device("cuda", 0)
+    B = cfg["batch"]
+    acts_np = wl.random_actions(cfg, 8, T, bad_fraction=0.03)
+    acts = torch.from_numpy(acts_np).to(dev)
+    roll, single, cpu = binding.Pcgrl(cfg, 0), binding.Pcgrl(cfg, 0), oracle.Oracle(cfg)
+    for e in (roll, single):
+        e.pcgrl_reset(21)
+    cpu.reset(21)
+    obs = torch.zeros((slots,) + roll.obs_shape, dtype=torch.uint8, device=dev)
+    rew = torch.empty((T, B), dtype=torch.float32, device=dev)
+    done = torch.empty((T, B), dtype=torch.uint8, device=dev)
+    roll.pcgrl_rollout(acts, obs, rew, done)
+    want_obs = {}
+    o1 = single.new_obs()
+    r1 = torch.empty(B, dtype=torch.float32, device=dev)
+    d1 = torch.empty(B, dtype=torch.uint8, device=dev)
+    for t in range(T):
+        o, r, d = cpu.step(acts_np[t])
+        want_obs[t % slots] = o
+        assert np.array_equal(rew[t].cpu().numpy(), r), f"reward step {t}"
+        assert np.array_equal(done[t].cpu().numpy(), d), f"done step {t}"
+        single.pcgrl_step(acts[t], o1, r1, d1)
+        assert torch.equal(r1, rew[t]) and torch.equal(d1, done[t])
+    for k, o in want_obs.items():
+        assert_same("obs", obs[k], o, f"slot {k}")
+    assert torch.equal(o1, obs[(T - 1) % slots])
+    assert_same("metrics", roll.pcgrl_metrics(), cpu.metrics(), "after rollout")
+    compare_state(roll, cpu, "after rollout")
+    assert roll.pcgrl_bad_action_count() == int(((acts_np < 0) | (acts_np >= roll.K)).sum())
+    # a second rollout continues from the stored state, and single steps continue after a rollout
+    acts2_np = wl.random_actions(cfg, 9, 11)
+    roll.pcgrl_rollout(torch.from_numpy(acts2_np).to(dev), None, None, None)
+    for t in range(11):
+        cpu.step(acts2_np[t], want_obs=False)
+    compare_state(roll, cpu, "after second rollout")
+    a3 = wl.random_actions(cfg, 10, 1)[0]
+    roll.pcgrl_step(torch.from_numpy(a3).to(dev), o1, r1, d1)
+    o, r, d = cpu.step(a3)
+    assert_same("obs", o1, o, "step after rollout")
+    assert np.array_equal(r1.cpu().numpy(), r)
+    assert_same("metrics", roll.pcgrl_metrics(), cpu.metrics(), "step after rollout")
+    for e in (roll, single):
+        e.close()
+
+
+def test_rollout_argument_errors():
+    env = binding.Pcgrl(wl.workload("maze16", batch=4), 0)
+    acts = torch.zeros((5, 4), dtype=torch.int32, device="cuda")
+    obs = torch.zeros((6,) + env.obs_shape, dtype=torch.uint8, device="cuda")
+    with pytest.raises(binding.PcgrlError):
+        env.pcgrl_rollout(acts, obs)                      # more slots than steps
+    with pytest.raises(binding.PcgrlError):
+        env.pcgrl_rollout(acts[0])                        # not [T, B]
+    assert env.L.pcgrl_rollout(env.h, None, 5, None, 1, None, None, None) == -1
+    assert env.L.pcgrl_rollout(env.h, acts.data_ptr(), 0, None, 1, None, None, None) == -2
+    env.close()
