@@ -62,6 +62,10 @@ extern "C" {
 #define PCGRL_REGIONS_INCREMENTAL 0 /* update the region count from floods around the edited cell */
 #define PCGRL_REGIONS_RECOUNT 1     /* flood every component again after each modifying edit */
 
+#define PCGRL_OBS_STORE_AUTO 0   /* choose from the size of one step's observations */
+#define PCGRL_OBS_STORE_CACHED 1 /* ordinary stores */
+#define PCGRL_OBS_STORE_STREAM 2 /* non-temporal stores */
+
 #define PCGRL_MAX_METRICS 16
 #define PCGRL_MAX_TILES 8
 
@@ -89,6 +93,7 @@ typedef struct {
   int32_t levels_per_wave; /* tuning only, results do not depend on it: 0 = automatic; 1, 2 or 4 =
                            how many levels share one 64-lane wavefront (at most 64 / S, S = 16, 32
                            or 64 covering max_h and max_w; larger requests are rounded down) */
+  int32_t obs_store_mode;  /* tuning only: PCGRL_OBS_STORE_* */
   uint32_t init_cdf[PCGRL_MAX_TILES]; /* non-decreasing cumulative tile probabilities scaled by
                            2^32 (entry k = P(tile <= k)); the last tile takes the rest; all zero =
                            start from an all-empty map                      (Methods / Task) */

@@ -58,6 +58,7 @@ int check_config(const pcgrl_config* c) {
   if (c->max_steps < 1 || c->max_changes < 0) return PCGRL_E_CONFIG;
   if (c->regions_mode != PCGRL_REGIONS_INCREMENTAL && c->regions_mode != PCGRL_REGIONS_RECOUNT) return PCGRL_E_CONFIG;
   if (c->levels_per_wave < 0 || c->levels_per_wave > 4) return PCGRL_E_CONFIG;
+  if (c->obs_store_mode < 0 || c->obs_store_mode > 2) return PCGRL_E_CONFIG;
   for (int k = 1; k < tiles_of(c->problem) - 1; ++k)
     if (c->init_cdf[k] < c->init_cdf[k - 1]) return PCGRL_E_CONFIG;
   return PCGRL_OK;
@@ -256,12 +257,17 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   a.nwaves = ctx->nwaves;
   a.envs_per_wave_log2 = ctx->epw == 4 ? 2 : ctx->epw == 2 ? 1 : 0;
   a.use_frozen = cfg->n_frozen > 0 ? 1 : 0;
-  // One step's observations are rewritten every step.  Up to a few hundred MB ordinary stores
-  // are faster (the 256 MB last-level cache absorbs most of them and keeps them for the
-  // consumer); well beyond it streaming stores reach HBM at a higher rate (measured: 504 MB per
-  // step, 163 us with ordinary stores, 111 us streamed).
-  a.stream_obs = (size_t)cfg->batch * E > ((size_t)448 << 20) ? 1 : 0;
-  a.lds_words = (int32_t)(ctx->lds_bytes / 4);
+  // How the observation is stored (measured on MI355X, see the design notes): streaming stores
+  // keep a small batch's level state in the 4 MB per-XCD L2 from one step to the next instead of
+  // evicting it with observation bytes nobody on that XCD reads again; from there up to a few
+  // hundred MB ordinary stores win because the 256 MB last-level cache absorbs them; far beyond
+  // it streaming stores reach HBM at a higher rate again.
+  {
+    const size_t obs_step_bytes = (size_t)cfg->batch * E;
+    a.stream_obs = (obs_step_bytes <= ((size_t)32 << 20) || obs_step_bytes > ((size_t)448 << 20)) ? 1 : 0;
+    if (cfg->obs_store_mode == PCGRL_OBS_STORE_CACHED) a.stream_obs = 0;
+    if (cfg->obs_store_mode == PCGRL_OBS_STORE_STREAM) a.stream_obs = 1;
+  }
   for (int k = 0; k < 8; ++k) a.cdf[k] = cfg->init_cdf[k];
   for (int i = 0; i < kMaxMetrics; ++i) {
     a.weights[i] = cfg->weights[i];

@@ -72,7 +72,8 @@ def cdf_from_probs(probs):
 def make_config(problem, batch, size, obs_w, *, min_size=None, pad_mode=PAD_BORDER,
                 pos_mode=POS_RANDOM, n_frozen=0, max_steps=1000, max_changes=0, autoreset=1,
                 probs=None, weights=None, target_lo=None, target_hi=None, max_w=None,
-                min_w=None, regions_mode=REGIONS_INCREMENTAL, levels_per_wave=0):
+                min_w=None, regions_mode=REGIONS_INCREMENTAL, levels_per_wave=0,
+                obs_store_mode=0):
     w, lo, hi = default_reward_table(problem)
     mh = size
     mw = size if max_w is None else max_w
@@ -91,6 +92,7 @@ def make_config(problem, batch, size, obs_w, *, min_size=None, pad_mode=PAD_BORD
         target_lo=pad16(target_lo if target_lo is not None else lo, 0)[:16],
         target_hi=pad16(target_hi if target_hi is not None else hi, 0)[:16],
         regions_mode=regions_mode, levels_per_wave=levels_per_wave,
+        obs_store_mode=obs_store_mode,
     )
 
 
