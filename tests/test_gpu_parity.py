@@ -278,3 +278,118 @@ def test_rollout_argument_errors():
     assert env.L.pcgrl_rollout(env.h, None, 5, None, 1, None, None, None) == -1
     assert env.L.pcgrl_rollout(env.h, acts.data_ptr(), 0, None, 1, None, None, None) == -2
     env.close()
+
+
+def _serpentine(n):
+    """n x n binary level: open even rows joined by single cells at alternating ends."""
+    t = np.ones((n, n), np.int8)
+    t[0::2, :] = 0
+    for k, y in enumerate(range(1, n - 1, 2)):
+        t[y, n - 1 if k % 2 == 0 else 0] = 0
+    return t
+
+
+def test_degenerate_and_extreme_levels():
+    """All-wall, all-empty, one-cell and one-row / one-column maps, and the longest possible
+    shortest path in a 64x64 buffer (a serpentine: 2078 edges, so the sweeps run ~1000 trips)."""
+    dev = torch.device("cuda", 0)
+    cases = []
+    n = 64
+    cases.append(("all wall", np.ones((n, n), np.int8), (n, n)))
+    cases.append(("all empty", np.zeros((n, n), np.int8), (n, n)))
+    cases.append(("serpentine", _serpentine(n), (n, n)))
+    one = np.full((n, n), -1, np.int8); one[0, 0] = 0
+    cases.append(("single cell", one, (1, 1)))
+    row = np.full((n, n), -1, np.int8); row[0, :] = 0; row[0, 31] = 1
+    cases.append(("one row", row, (1, n)))
+    col = np.full((n, n), -1, np.int8); col[:, 0] = 0
+    cases.append(("one column", col, (n, 1)))
+    checker = ((np.add.outer(np.arange(n), np.arange(n)) % 2) == 1).astype(np.int8)
+    cases.append(("checkerboard", checker, (n, n)))
+    B = len(cases)
+    cfg = wl.make_config(wl.BINARY, B, n, 63, min_size=1, autoreset=0, max_steps=10**6, pos_mode=wl.POS_SCAN)
+    for lpw, rmode in ((0, wl.REGIONS_INCREMENTAL), (0, wl.REGIONS_RECOUNT)):
+        gpu = binding.Pcgrl(dict(cfg, regions_mode=rmode, levels_per_wave=lpw), 0)
+        cpu = oracle.Oracle(cfg)
+        tiles = np.stack([c[1] for c in cases])
+        hw = np.array([c[2] for c in cases], np.int16)
+        pos = np.zeros((B, 2), np.int16)
+        gpu.pcgrl_reset(1)
+        cpu.reset(1)
+        gpu.pcgrl_set_state(torch.from_numpy(tiles).to(dev), None, torch.from_numpy(hw).to(dev),
+                            torch.from_numpy(pos).to(dev))
+        cpu.set_state(tiles, None, hw, pos)
+        m = gpu.pcgrl_metrics().cpu().numpy()
+        assert_same("metrics", m, cpu.metrics(), "degenerate levels")
+        assert list(m[:3, 0]) == [0, 1, 1] and list(m[:3, 1]) == [0, 126, 2078]
+        assert m[3, 0] == 1 and m[3, 1] == 0 and m[6, 0] == n * n // 2 and m[6, 1] == 0
+        assert_same("obs", gpu.pcgrl_observe(), cpu.observe(), "degenerate levels")
+        rew = torch.empty(B, dtype=torch.float32, device=dev)
+        obs = gpu.new_obs()
+        for t in range(70):                      # flip the cell under the scanning agent
+            st = cpu.get_state()
+            cur = st["tiles"][np.arange(B), st["pos"][:, 0], st["pos"][:, 1]]
+            a = (1 - cur).astype(np.int32)
+            gpu.pcgrl_step(torch.from_numpy(a).to(dev), obs, rew, None)
+            o, r, _ = cpu.step(a)
+            assert_same("metrics", gpu.pcgrl_metrics(), cpu.metrics(), f"flip {t}")
+            assert np.array_equal(rew.cpu().numpy(), r), f"flip {t}"
+            assert_same("obs", obs, o, f"flip {t}")
+        compare_state(gpu, cpu, "after flips")
+        gpu.close()
+
+
+def test_small_buffers_and_every_window_size():
+    """Buffers smaller than a lane group (5x3, 1x1) and every window size 1..63 on a 16x16 maze."""
+    run_parity(wl.make_config(wl.MAZE, 9, 5, 7, max_w=3, min_size=1, min_w=1, max_steps=11), 40, label="5x3 buffer")
+    run_parity(wl.make_config(wl.DUNGEON, 3, 1, 3, max_steps=5), 12, label="1x1 buffer")
+    dev = torch.device("cuda", 0)
+    for ow in range(1, 64):
+        cfg = wl.make_config(wl.MAZE, 6, 16, ow, min_size=9, max_steps=4, pad_mode=ow % 2,
+                             levels_per_wave=(0, 2, 4)[ow % 3])
+        gpu, cpu = binding.Pcgrl(cfg, 0), oracle.Oracle(cfg)
+        obs = gpu.new_obs()
+        gpu.pcgrl_reset(ow, obs)
+        assert_same("obs", obs, cpu.reset(ow), f"ow={ow} reset")
+        acts = wl.random_actions(cfg, ow, 6)
+        for t in range(6):
+            gpu.pcgrl_step(torch.from_numpy(acts[t]).to(dev), obs)
+            o, _, _ = cpu.step(acts[t])
+            assert_same("obs", obs, o, f"ow={ow} step {t}")
+        gpu.close()
+
+
+def test_largest_batch_spot_check():
+    """2^20 binary levels: one reset and two steps; everything compared on a strided sample of
+    environments (the oracle takes the same global environment indices through set_state)."""
+    dev = torch.device("cuda", 0)
+    B = 1 << 20
+    cfg = wl.workload("binary16", batch=B, max_steps=50)
+    gpu = binding.Pcgrl(cfg, 0)
+    obs = gpu.new_obs()
+    rew = torch.empty(B, dtype=torch.float32, device=dev)
+    done = torch.empty(B, dtype=torch.uint8, device=dev)
+    gpu.pcgrl_reset(3, obs)
+    idx = np.arange(0, B, 4099)
+    idx = np.concatenate([idx, [B - 3, B - 2, B - 1]])
+    st0 = {k: v[torch.from_numpy(idx).to(dev)].cpu().numpy() for k, v in gpu.pcgrl_get_state().items()}
+    cpu = oracle.Oracle(dict(cfg, batch=len(idx)))
+    cpu.reset(0)
+    cpu.set_state(st0["tiles"], st0["frozen"], st0["hw"], st0["pos"])
+    tidx = torch.from_numpy(idx).to(dev)
+    assert_same("metrics", gpu.pcgrl_metrics()[tidx], cpu.metrics(), "2^20 after reset")
+    assert_same("obs", obs[tidx], cpu.observe(), "2^20 after reset")
+    acts = wl.random_actions(cfg, 1, 1)[0]
+    gpu.pcgrl_step(torch.from_numpy(acts).to(dev), obs, rew, done)
+    _, r, d = cpu.step(acts[idx], want_obs=False)
+    assert np.array_equal(rew[tidx].cpu().numpy(), r)
+    assert_same("metrics", gpu.pcgrl_metrics()[tidx], cpu.metrics(), "2^20 after a step")
+    g = gpu.pcgrl_get_state()
+    assert_same("tiles", g["tiles"][tidx], cpu.get_state()["tiles"], "2^20 after a step")
+    # the observation is centred on the GPU's own (seeded) next position: check it structurally
+    o = obs[tidx].cpu().numpy()
+    assert (o.sum(axis=1) == 1).all()
+    pos = g["pos"][tidx].cpu().numpy()
+    t = g["tiles"][tidx].cpu().numpy()
+    assert (o[np.arange(len(idx)), t[np.arange(len(idx)), pos[:, 0], pos[:, 1]], 15, 15] == 1).all()
+    gpu.close()
