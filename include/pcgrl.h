@@ -100,10 +100,20 @@ typedef struct {
   float weights[PCGRL_MAX_METRICS];     /* reward weight of each metric      (Methods / Training) */
   int32_t target_lo[PCGRL_MAX_METRICS]; /* default target range of each metric (clamped to */
   int32_t target_hi[PCGRL_MAX_METRICS]; /* 0..65535); the loss of a metric v is max(0, lo - v, v - hi) */
+  int32_t pinpoint_tile[8]; /* tile id written to the j-th pinpoint cell when an episode starts, so
+                           that pivotal tiles (player, door, key) sit frozen at seeded cells;
+                           -1 keeps the tile drawn there               (Task / Pinpoint tiles) */
+  uint32_t ctrl_mask;   /* bit i set: metric i is controlled -- at every episode start its target
+                           becomes one value drawn uniformly from [ctrl_lo[i], ctrl_hi[i]]
+                           (0 <= lo <= hi <= 65535), lo = hi = that value  (Methods / Training:
+                           the user or a curriculum varies target path length or nearest enemy) */
+  int32_t ctrl_lo[PCGRL_MAX_METRICS];
+  int32_t ctrl_hi[PCGRL_MAX_METRICS];
 } pcgrl_config;
 
 /* Fills *cfg with this library's defaults for a problem: fixed 16x16 map, window 31, border
- * padding, scan order, no pinpoints, 1000 steps, autoreset, uniform initial tiles, and the reward
+ * padding, scan order, no pinpoints, no controlled metric, 1000 steps, autoreset, uniform initial
+ * tiles, and the reward
  * table (one region, path as long as possible, one player / key / door, 2..5 enemies, nearest
  * enemy >= 4).  cfg: host pointer. */
 int pcgrl_config_default(int32_t problem, pcgrl_config* cfg);
@@ -173,8 +183,13 @@ int pcgrl_set_state(pcgrl_ctx* ctx, const int8_t* tiles, const uint8_t* frozen, 
 /* Per-environment target ranges (control targets of Methods / Training).
  * targets: device, int32 [batch][M][2] = (lo, hi), each clamped to 0..65535 (no metric of a
  * 64x64 level exceeds 4096).  They stay in force until the next pcgrl_reset, which restores the
- * configuration's defaults. */
+ * configuration's defaults; the targets of controlled metrics (ctrl_mask) are redrawn whenever an
+ * episode starts. */
 int pcgrl_set_targets(pcgrl_ctx* ctx, const int32_t* targets, void* stream);
+
+/* Copies the target ranges now in force (a policy conditioned on control targets reads them
+ * here).  out: device, int32 [batch][M][2]. */
+int pcgrl_get_targets(pcgrl_ctx* ctx, int32_t* out, void* stream);
 
 /* Shape queries (host side, no GPU work).  out: host pointer to 4 ints = batch, C, obs_w, obs_w. */
 int pcgrl_obs_shape(const pcgrl_ctx* ctx, int32_t out[4]);

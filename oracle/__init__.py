@@ -35,6 +35,10 @@ class OrcConfig(C.Structure):
         ("weights", C.c_float * MAX_METRICS),
         ("target_lo", C.c_int32 * MAX_METRICS),
         ("target_hi", C.c_int32 * MAX_METRICS),
+        ("pinpoint_tile", C.c_int32 * 8),
+        ("ctrl_mask", C.c_uint32),
+        ("ctrl_lo", C.c_int32 * MAX_METRICS),
+        ("ctrl_hi", C.c_int32 * MAX_METRICS),
     ]
 
 
@@ -67,6 +71,7 @@ def lib():
         L.orc_get_state.argtypes = [p, p, p, p, p, p]
         L.orc_set_state.argtypes = [p, p, p, p, p]
         L.orc_set_targets.argtypes = [p, p]
+        L.orc_get_targets.argtypes = [p, p]
         L.orc_mix64.restype = C.c_uint64
         L.orc_mix64.argtypes = [C.c_uint64]
         L.orc_env_key.restype = C.c_uint64
@@ -98,7 +103,7 @@ def make_config(d: dict) -> OrcConfig:
     for k, v in d.items():
         if k not in known:      # knobs of other implementations (e.g. how regions are counted)
             continue
-        if k in ("init_cdf", "weights", "target_lo", "target_hi"):
+        if k in ("init_cdf", "weights", "target_lo", "target_hi", "pinpoint_tile", "ctrl_lo", "ctrl_hi"):
             arr = getattr(c, k)
             for i, x in enumerate(v):
                 arr[i] = x
@@ -176,6 +181,11 @@ class Oracle:
         assert tiles.shape == (self.B, self.Hm, self.Wm)
         assert hw.shape == (self.B, 2) and pos.shape == (self.B, 2)
         self.L.orc_set_state(self.h, _ptr(tiles), _ptr(frozen), _ptr(hw), _ptr(pos))
+
+    def get_targets(self):
+        out = np.zeros((self.B, self.M, 2), np.int32)
+        self.L.orc_get_targets(self.h, _ptr(out))
+        return out
 
     def set_targets(self, targets):
         targets = np.ascontiguousarray(targets, np.int32)

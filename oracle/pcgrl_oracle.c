@@ -92,7 +92,8 @@ uint64_t orc_env_key(uint64_t seed, uint64_t env, uint64_t episode) {
 }
 
 /* stream 0: shape (counter 0 = height, 1 = width); 1: tiles (counter = y*max_w+x);
- * 2: pinpoint positions (counter = attempt); 3: agent position (counter = t). */
+ * 2: pinpoint positions (counter = attempt); 3: agent position (counter = t);
+ * 4: control targets (counter = metric index). */
 uint64_t orc_draw(uint64_t key, uint32_t stream, uint32_t counter) {
   uint64_t c = ((uint64_t)stream << 32) + (uint64_t)counter + 1;
   return orc_mix64(key + GOLDEN * c);
@@ -283,6 +284,10 @@ static int cfg_ok(const orc_config* c) {
   if (c->pos_mode != ORC_POS_SCAN && c->pos_mode != ORC_POS_RANDOM) return 0;
   if (c->n_frozen < 0 || c->n_frozen > 8 || c->n_frozen > c->min_h * c->min_w) return 0;
   if (c->max_steps < 1 || c->max_changes < 0) return 0;
+  for (int j = 0; j < 8; ++j)
+    if (c->pinpoint_tile[j] < -1 || c->pinpoint_tile[j] >= orc_num_tiles(c->problem)) return 0;
+  for (int i = 0; i < orc_num_metrics(c->problem); ++i)
+    if (((c->ctrl_mask >> i) & 1u) && (c->ctrl_lo[i] < 0 || c->ctrl_hi[i] < c->ctrl_lo[i] || c->ctrl_hi[i] > 65535)) return 0;
   return 1;
 }
 
@@ -363,10 +368,19 @@ static void env_begin_episode(const orc_ctx* ctx, int b, int episode) {
     uint64_t u = orc_draw(key, 2, a);
     int y = below(hi32(u), e->h), x = below(lo32(u), e->w);
     if (!e->frozen[y * c->max_w + x]) {
+      /* Task / Pinpoint tiles: a pivotal tile (player, door, ...) frozen at an arbitrary cell */
       e->frozen[y * c->max_w + x] = 1;
+      if (c->pinpoint_tile[placed] >= 0) e->tiles[y * c->max_w + x] = (int8_t)c->pinpoint_tile[placed];
       ++placed;
     }
   }
+  /* Methods / Training: the target of a controlled metric varies from episode to episode */
+  for (int i = 0; i < ctx->M; ++i)
+    if ((c->ctrl_mask >> i) & 1u) {
+      int v = c->ctrl_lo[i] + below(hi32(orc_draw(key, 4, (uint32_t)i)), c->ctrl_hi[i] - c->ctrl_lo[i] + 1);
+      e->tgt[i][0] = v;
+      e->tgt[i][1] = v;
+    }
 
   e->t = 0;
   e->n_changes = 0;
@@ -523,6 +537,14 @@ void orc_set_state(orc_ctx* ctx, const int8_t* tiles, const uint8_t* frozen, con
     e->n_changes = 0;
     env_metrics(ctx, e);
   }
+}
+
+void orc_get_targets(const orc_ctx* ctx, int32_t* targets) {
+  for (int b = 0; b < ctx->cfg.batch; ++b)
+    for (int i = 0; i < ctx->M; ++i) {
+      targets[((size_t)b * ctx->M + i) * 2] = ctx->env[b].tgt[i][0];
+      targets[((size_t)b * ctx->M + i) * 2 + 1] = ctx->env[b].tgt[i][1];
+    }
 }
 
 void orc_set_targets(orc_ctx* ctx, const int32_t* targets) {

@@ -60,6 +60,10 @@ typedef struct {
   float weights[ORC_MAX_METRICS];
   int32_t target_lo[ORC_MAX_METRICS];
   int32_t target_hi[ORC_MAX_METRICS];
+  int32_t pinpoint_tile[8]; /* tile written to the j-th pinpoint cell at episode start; -1 keeps the drawn tile */
+  uint32_t ctrl_mask;       /* bit i: metric i's target is drawn anew every episode ... */
+  int32_t ctrl_lo[ORC_MAX_METRICS]; /* ... uniformly from [ctrl_lo[i], ctrl_hi[i]] and used as an */
+  int32_t ctrl_hi[ORC_MAX_METRICS]; /* exact target (lo = hi = the drawn value) */
 } orc_config;
 
 typedef struct orc_ctx orc_ctx;
@@ -90,6 +94,7 @@ void orc_get_state(const orc_ctx* ctx, int8_t* tiles, uint8_t* frozen, int16_t* 
 void orc_set_state(orc_ctx* ctx, const int8_t* tiles, const uint8_t* frozen, const int16_t* hw,
                    const int16_t* pos);
 void orc_set_targets(orc_ctx* ctx, const int32_t* targets /* [batch][M][2] */);
+void orc_get_targets(const orc_ctx* ctx, int32_t* targets /* [batch][M][2] */);
 
 /* ---- building blocks, exported so that tests can pin each one on its own ---- */
 uint64_t orc_mix64(uint64_t z);

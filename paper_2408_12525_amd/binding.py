@@ -30,12 +30,17 @@ class PcgrlConfig(C.Structure):
         ("weights", C.c_float * MAX_METRICS),
         ("target_lo", C.c_int32 * MAX_METRICS),
         ("target_hi", C.c_int32 * MAX_METRICS),
+        ("pinpoint_tile", C.c_int32 * 8),
+        ("ctrl_mask", C.c_uint32),
+        ("ctrl_lo", C.c_int32 * MAX_METRICS),
+        ("ctrl_hi", C.c_int32 * MAX_METRICS),
     ]
 
 
 EXPORTS = [
     "pcgrl_config_default", "pcgrl_create", "pcgrl_destroy", "pcgrl_reset", "pcgrl_step", "pcgrl_rollout",
     "pcgrl_metrics", "pcgrl_observe", "pcgrl_get_state", "pcgrl_set_state", "pcgrl_set_targets",
+    "pcgrl_get_targets",
     "pcgrl_obs_shape", "pcgrl_num_metrics", "pcgrl_num_tiles", "pcgrl_bad_action_count",
     "pcgrl_selftest", "pcgrl_strerror",
 ]
@@ -73,6 +78,7 @@ def load():
     L.pcgrl_get_state.argtypes = [p, p, p, p, p, p, p]
     L.pcgrl_set_state.argtypes = [p, p, p, p, p, p]
     L.pcgrl_set_targets.argtypes = [p, p, p]
+    L.pcgrl_get_targets.argtypes = [p, p, p]
     L.pcgrl_obs_shape.argtypes = [p, C.POINTER(i32 * 4)]
     L.pcgrl_num_metrics.argtypes = [p]
     L.pcgrl_num_tiles.argtypes = [p]
@@ -92,7 +98,7 @@ def _check(rc: int, what: str):
 def make_config(d: dict) -> PcgrlConfig:
     c = PcgrlConfig()
     for k, v in d.items():
-        if k in ("init_cdf", "weights", "target_lo", "target_hi"):
+        if k in ("init_cdf", "weights", "target_lo", "target_hi", "pinpoint_tile", "ctrl_lo", "ctrl_hi"):
             arr = getattr(c, k)
             for i, x in enumerate(v):
                 arr[i] = x
@@ -227,6 +233,13 @@ class Pcgrl:
     def pcgrl_set_targets(self, targets):
         t = self._dev(targets, torch.int32, (self.B, self.M, 2), "targets")
         _check(self.L.pcgrl_set_targets(self.h, t, self._st()), "pcgrl_set_targets")
+
+    def pcgrl_get_targets(self, out=None):
+        if out is None:
+            out = torch.empty((self.B, self.M, 2), dtype=torch.int32, device=self.device)
+        o = self._dev(out, torch.int32, (self.B, self.M, 2), "out")
+        _check(self.L.pcgrl_get_targets(self.h, o, self._st()), "pcgrl_get_targets")
+        return out
 
     def pcgrl_bad_action_count(self) -> int:
         n = C.c_uint64(0)

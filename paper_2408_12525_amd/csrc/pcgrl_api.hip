@@ -59,6 +59,11 @@ int check_config(const pcgrl_config* c) {
   if (c->regions_mode != PCGRL_REGIONS_INCREMENTAL && c->regions_mode != PCGRL_REGIONS_RECOUNT) return PCGRL_E_CONFIG;
   if (c->levels_per_wave < 0 || c->levels_per_wave > 4) return PCGRL_E_CONFIG;
   if (c->obs_store_mode < 0 || c->obs_store_mode > 2) return PCGRL_E_CONFIG;
+  for (int j = 0; j < 8; ++j)
+    if (c->pinpoint_tile[j] < -1 || c->pinpoint_tile[j] >= tiles_of(c->problem)) return PCGRL_E_CONFIG;
+  for (int i = 0; i < metrics_of(c->problem); ++i)
+    if (((c->ctrl_mask >> i) & 1u) && (c->ctrl_lo[i] < 0 || c->ctrl_hi[i] < c->ctrl_lo[i] || c->ctrl_hi[i] > 65535))
+      return PCGRL_E_CONFIG;
   for (int k = 1; k < tiles_of(c->problem) - 1; ++k)
     if (c->init_cdf[k] < c->init_cdf[k - 1]) return PCGRL_E_CONFIG;
   return PCGRL_OK;
@@ -135,6 +140,7 @@ int pcgrl_config_default(int32_t problem, pcgrl_config* cfg) {
   cfg->max_steps = 1000;
   cfg->autoreset = 1;
   cfg->regions_mode = PCGRL_REGIONS_INCREMENTAL;
+  for (int j = 0; j < 8; ++j) cfg->pinpoint_tile[j] = -1;
   for (int k = 0; k < K; ++k)
     cfg->init_cdf[k] = k == K - 1 ? 0xFFFFFFFFu : (uint32_t)(((uint64_t)(k + 1) << 32) / (uint64_t)K);
   const int BIG = 64 * 64;  // no path is this long: "as long as possible"
@@ -273,7 +279,11 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
     a.weights[i] = cfg->weights[i];
     a.target_lo[i] = cfg->target_lo[i];
     a.target_hi[i] = cfg->target_hi[i];
+    a.ctrl_lo[i] = cfg->ctrl_lo[i];
+    a.ctrl_hi[i] = cfg->ctrl_hi[i];
   }
+  for (int j = 0; j < 8; ++j) a.pinpoint_tile[j] = cfg->pinpoint_tile[j];
+  a.ctrl_mask = cfg->ctrl_mask & ((1u << ctx->M) - 1u);
 
   rc = launch_init(ctx, kInitGenerate | kInitMetrics | kInitTargets, 0, nullptr, nullptr);
   if (rc == PCGRL_OK && hipDeviceSynchronize() != hipSuccess) rc = PCGRL_E_HIP;
@@ -387,6 +397,16 @@ int pcgrl_set_targets(pcgrl_ctx* ctx, const int32_t* targets, void* stream) {
   hipLaunchKernelGGL(set_targets_kernel, dim3((n + 255) / 256), dim3(256), 0,
                      static_cast<hipStream_t>(stream), targets, static_cast<uint32_t*>(ctx->d_targets),
                      ctx->cfg.batch, ctx->M);
+  return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
+}
+
+int pcgrl_get_targets(pcgrl_ctx* ctx, int32_t* out, void* stream) {
+  if (!ctx || !out) return PCGRL_E_NULL;
+  DeviceGuard guard(ctx->device);
+  const int n = ctx->cfg.batch * ctx->M;
+  hipLaunchKernelGGL(get_targets_kernel, dim3((n + 255) / 256), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const uint32_t*>(ctx->d_targets),
+                     out, ctx->cfg.batch, ctx->M);
   return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
 }
 

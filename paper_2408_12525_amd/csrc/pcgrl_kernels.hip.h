@@ -67,6 +67,9 @@ struct KArgs {
   uint32_t cdf[8];
   float weights[kMaxMetrics];
   int32_t target_lo[kMaxMetrics], target_hi[kMaxMetrics];
+  int32_t pinpoint_tile[8];
+  uint32_t ctrl_mask;
+  int32_t ctrl_lo[kMaxMetrics], ctrl_hi[kMaxMetrics];
 };
 
 template <int S> struct RowWord { using T = uint32_t; };
@@ -427,6 +430,12 @@ __device__ __forceinline__ uint32_t pack_range(int lo, int hi) {
   return (uint32_t)min(max(lo, 0), 65535) | ((uint32_t)min(max(hi, 0), 65535) << 16);
 }
 
+// Target of a controlled metric for the episode with generator key `key` (Methods / Training).
+__device__ __forceinline__ uint32_t control_target(const KArgs& a, uint64_t key, int i) {
+  int v = a.ctrl_lo[i] + below((uint32_t)(draw(key, 4, (uint32_t)i) >> 32), a.ctrl_hi[i] - a.ctrl_lo[i] + 1);
+  return pack_range(v, v);
+}
+
 // ---------------------------------------------------------------- episodes
 
 // Start of an episode: shape, tiles, pinpoints, first position, all from the env's key.
@@ -464,7 +473,16 @@ __device__ __forceinline__ void begin_episode(const KArgs& a, const Lanes<S>& L,
     bool mine = L.y == fy;
     bool fresh = L.gany(mine && ((fz >> fx) & 1) == 0);
     if (fresh) {
-      if (mine) fz |= (W)1 << fx;
+      int ptile = -1;  // Task / Pinpoint tiles: a pivotal tile frozen at this cell
+#pragma unroll
+      for (int j = 0; j < 8; ++j) ptile = placed == j ? a.pinpoint_tile[j] : ptile;
+      if (mine) {
+        fz |= (W)1 << fx;
+        if (ptile >= 0) {
+#pragma unroll
+          for (int i = 0; i < PR::P; ++i) p[i] = (p[i] & ~((W)1 << fx)) | ((W)((ptile >> i) & 1) << fx);
+        }
+      }
       ++placed;
     }
   }
@@ -728,8 +746,11 @@ __global__ __launch_bounds__(kMaxBlock) void init_kernel(KArgs a) {
     full_metrics<S, PROBLEM>(L, p, inside, wm.valid, m);
     if (wm.primary && L.y == 0) store_metrics<S, PROBLEM>(a.metrics + (size_t)wm.env * kMaxMetrics, m);
   }
-  if ((a.flags & kInitTargets) && wm.primary && L.y < PR::M)
-    a.targets[(size_t)wm.env * kMaxMetrics + L.y] = pack_range(a.target_lo[L.y], a.target_hi[L.y]);
+  if ((a.flags & kInitTargets) && wm.primary && L.y < PR::M) {
+    uint32_t t = pack_range(a.target_lo[L.y], a.target_hi[L.y]);
+    if ((a.ctrl_mask >> L.y) & 1u) t = control_target(a, er.key, L.y);
+    a.targets[(size_t)wm.env * kMaxMetrics + L.y] = t;
+  }
   if ((a.flags & kInitObs) && a.obs != nullptr) observe<S, PROBLEM>(a, L, wm, a.obs, p, inside, py, px);
 }
 
@@ -777,7 +798,7 @@ __global__ __launch_bounds__(kMaxBlock) void step_kernel(KArgs a) {
   int h = er.h, w = er.w, py = er.py, px = er.px;
   W inside = inside_row<W>(L.y, h, w);
   bool planes_dirty = false, fz_dirty = false;  // ROLL: what has to be written back at the end
-  bool metrics_dirty = false;
+  bool metrics_dirty = false, targets_dirty = false;
   W next_fz_row = 0;
 
   const int nsteps = ROLL ? a.rollout_steps : 1;
@@ -935,6 +956,12 @@ __global__ __launch_bounds__(kMaxBlock) void step_kernel(KArgs a) {
         planes_dirty = true;
         fz_dirty = true;
         metrics_dirty = true;
+        if (a.ctrl_mask != 0) {
+#pragma unroll
+          for (int i = 0; i < PR::M; ++i)
+            if ((a.ctrl_mask >> i) & 1u) tg[i] = control_target(a, nkey, i);
+          targets_dirty = true;
+        }
 #pragma unroll
         for (int i = 0; i < PR::M; ++i) mn[i] = nm[i];
         inside = ninside;
@@ -983,6 +1010,11 @@ __global__ __launch_bounds__(kMaxBlock) void step_kernel(KArgs a) {
     er.cell_frozen = (uint32_t)((next_fz_row >> px) & 1);
     a.env[wm.env] = er;
     if (metrics_dirty) store_metrics<S, PROBLEM>(a.metrics + (size_t)wm.env * kMaxMetrics, mo);
+    if (targets_dirty) {
+      uint4* tv = reinterpret_cast<uint4*>(a.targets + (size_t)wm.env * kMaxMetrics);
+#pragma unroll
+      for (int q = 0; q < kTg / 4; ++q) tv[q] = make_uint4(tg[4 * q], tg[4 * q + 1], tg[4 * q + 2], tg[4 * q + 3]);
+    }
   }
 }
 
@@ -1071,6 +1103,14 @@ __global__ void set_targets_kernel(const int32_t* src, uint32_t* dst, int B, int
   if (idx >= B * M) return;
   int env = idx / M, i = idx % M;
   dst[(size_t)env * kMaxMetrics + i] = pack_range(src[2 * idx], src[2 * idx + 1]);
+}
+
+__global__ void get_targets_kernel(const uint32_t* src, int32_t* dst, int B, int M) {
+  int idx = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+  if (idx >= B * M) return;
+  uint32_t t = src[(size_t)(idx / M) * kMaxMetrics + idx % M];
+  dst[2 * idx] = (int32_t)(t & 0xffffu);
+  dst[2 * idx + 1] = (int32_t)(t >> 16);
 }
 
 // Cross-lane exchange check: the DPP shifts against the plain shuffle definition.

@@ -73,7 +73,9 @@ def make_config(problem, batch, size, obs_w, *, min_size=None, pad_mode=PAD_BORD
                 pos_mode=POS_RANDOM, n_frozen=0, max_steps=1000, max_changes=0, autoreset=1,
                 probs=None, weights=None, target_lo=None, target_hi=None, max_w=None,
                 min_w=None, regions_mode=REGIONS_INCREMENTAL, levels_per_wave=0,
-                obs_store_mode=0):
+                obs_store_mode=0, pinpoint_tile=None, ctrl=None):
+    """ctrl: {metric index: (lo, hi)} -- targets drawn per episode; pinpoint_tile: tile of each
+    pinpoint (-1 keeps the drawn one)."""
     w, lo, hi = default_reward_table(problem)
     mh = size
     mw = size if max_w is None else max_w
@@ -83,6 +85,8 @@ def make_config(problem, batch, size, obs_w, *, min_size=None, pad_mode=PAD_BORD
     if probs is None:                       # probs="empty" starts from an all-empty map
         probs = [1.0 / K] * K
     pad16 = lambda v, z: list(v) + [z] * (16 - len(v))
+    ctrl = ctrl or {}
+    pin = list(pinpoint_tile or []) + [-1] * 8
     return dict(
         problem=problem, batch=batch, max_h=mh, max_w=mw, min_h=nh, min_w=nw, obs_w=obs_w,
         pad_mode=pad_mode, pos_mode=pos_mode, n_frozen=n_frozen, max_steps=max_steps,
@@ -93,6 +97,10 @@ def make_config(problem, batch, size, obs_w, *, min_size=None, pad_mode=PAD_BORD
         target_hi=pad16(target_hi if target_hi is not None else hi, 0)[:16],
         regions_mode=regions_mode, levels_per_wave=levels_per_wave,
         obs_store_mode=obs_store_mode,
+        pinpoint_tile=pin[:8],
+        ctrl_mask=sum(1 << i for i in ctrl),
+        ctrl_lo=[ctrl.get(i, (0, 0))[0] for i in range(16)],
+        ctrl_hi=[ctrl.get(i, (0, 0))[1] for i in range(16)],
     )
 
 
@@ -111,6 +119,12 @@ def workload(name: str, batch: int | None = None, **over):
     elif name == "dungeon32":   # 7-tile dungeon
         c = make_config(DUNGEON, 16384, 32, 15, max_steps=1000,
                         probs=[.40, .40, .04, .04, .04, .04, .04])
+    elif name == "maze16_pinpoint":   # empty start, frozen player and door, random shape 3..16
+        c = make_config(MAZE, 4096, 16, 8, min_size=3, probs="empty", n_frozen=2, pinpoint_tile=[2, 3],
+                        max_steps=1000)
+    elif name == "dungeon16_ctrl":    # dungeon with a controllable path length and nearest enemy
+        c = make_config(DUNGEON, 4096, 16, 31, max_steps=1000, n_frozen=3, pinpoint_tile=[2, 3, 4],
+                        probs=[.40, .40, .04, .04, .04, .04, .04], ctrl={1: (10, 60), 2: (2, 9)})
     else:
         raise KeyError(name)
     if batch is not None:

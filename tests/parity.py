@@ -68,3 +68,4 @@ def compare_state(gpu, cpu, ctx):
     c = cpu.get_state()
     for k in ("hw", "pos", "counters", "tiles", "frozen"):
         assert_same(k, g[k], c[k], ctx)
+    assert_same("targets", gpu.pcgrl_get_targets(), cpu.get_targets(), ctx)

@@ -39,6 +39,11 @@ SMALL = [
     ("binary64 sparse walls", wl.make_config(wl.BINARY, 6, 64, 31, max_steps=90, probs=[.8, .2]), 120, {}),
     ("dungeon64 ow1", wl.make_config(wl.DUNGEON, 4, 40, 1, max_w=64, max_steps=90), 100, {}),
     ("batch of one", wl.make_config(wl.MAZE, 1, 16, 31, max_steps=30), 70, {}),
+    ("maze16 pinpointed player and door", wl.workload("maze16_pinpoint", batch=90, max_steps=33), 120, {}),
+    ("dungeon16 control targets", wl.workload("dungeon16_ctrl", batch=50, max_steps=27), 120, {}),
+    ("maze32 pinpoints + control, scan", wl.make_config(wl.MAZE, 30, 32, 16, min_size=3, probs="empty", n_frozen=4,
+                                                         pinpoint_tile=[2, 3, -1, 1], ctrl={1: (5, 40), 0: (1, 3)},
+                                                         pos_mode=wl.POS_SCAN, max_steps=41), 130, {}),
     ("no autoreset", wl.make_config(wl.BINARY, 10, 16, 7, max_steps=20, autoreset=0), 50, {}),
 ]
 
@@ -213,6 +218,8 @@ ROLLOUTS = [
     ("dungeon32 lpw2", wl.workload("dungeon32", batch=21, max_steps=26, levels_per_wave=2), 40, 1),
     ("maze64", wl.workload("maze64", batch=9, max_steps=17), 40, 40),
     ("binary64 budget", wl.make_config(wl.BINARY, 5, 64, 63, min_size=40, n_frozen=5, max_changes=9, max_steps=100), 60, 3),
+    ("dungeon16 control targets", wl.workload("dungeon16_ctrl", batch=40, max_steps=13), 60, 2),
+    ("maze16 pinpointed", wl.workload("maze16_pinpoint", batch=40, max_steps=19), 60, 60),
 ]
 
 

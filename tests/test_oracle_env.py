@@ -244,3 +244,53 @@ def test_set_state_installs_a_level_and_recomputes_metrics():
     assert m2[0, 1] == 4 and r[0] == 2.0 * (4 - 8)
     # env 1 walls off (2,3)... already a wall: no-op
     assert r[1] == 0 and (m2[1] == m[1]).all()
+
+
+def test_pinpoint_tiles_are_placed_frozen_and_survive_every_edit():
+    # Task / Pinpoint tiles: player and door frozen at seeded cells of an otherwise empty map
+    cfg = wl.workload("maze16_pinpoint", batch=40, max_steps=60)
+    env, _, acts = run(cfg, 150)
+    for t, a in enumerate(acts):
+        st = env.get_state()
+        fr = st["frozen"].astype(bool)
+        assert (fr.sum(axis=(1, 2)) == 2).all()
+        for b in range(env.B):
+            assert sorted(st["tiles"][b][fr[b]].tolist()) == [2, 3]
+            if st["counters"][b, 0] == 0:                      # first state of an episode
+                h, w = st["hw"][b]
+                assert (st["tiles"][b, :h, :w][~fr[b, :h, :w]] == 0).all()
+        env.step(a, want_obs=False)
+
+
+def test_control_targets_are_redrawn_per_episode_inside_their_range():
+    cfg = wl.workload("dungeon16_ctrl", batch=300, max_steps=5)
+    env = oracle.Oracle(cfg)
+    env.reset(4)
+    seen_path, seen_enemy = set(), set()
+    prev = env.get_targets()
+    lo_hi = np.stack([cfg["target_lo"][:10], cfg["target_hi"][:10]], axis=1)
+    for t in range(1, 16):
+        env.step(np.zeros(env.B, np.int32), want_obs=False)
+        tg = env.get_targets()
+        assert (tg[:, 1, 0] == tg[:, 1, 1]).all() and (tg[:, 2, 0] == tg[:, 2, 1]).all()
+        assert tg[:, 1, 0].min() >= 10 and tg[:, 1, 0].max() <= 60
+        assert tg[:, 2, 0].min() >= 2 and tg[:, 2, 0].max() <= 9
+        others = [i for i in range(10) if i not in (1, 2)]
+        assert (tg[:, others] == lo_hi[others]).all()
+        if t % 5:
+            assert (tg == prev).all()                         # unchanged inside an episode
+        else:
+            assert (tg[:, 1] != prev[:, 1]).any()             # new episode, new draw
+        prev = tg
+        seen_path.update(tg[:, 1, 0].tolist())
+        seen_enemy.update(tg[:, 2, 0].tolist())
+    assert seen_path == set(range(10, 61)) and seen_enemy == set(range(2, 10))
+    # the reward follows the drawn target: loss = |path - target|
+    cfg1 = wl.make_config(wl.MAZE, 1, 8, 3, min_size=1, autoreset=0, ctrl={1: (3, 3)}, weights=[0, 1, 0, 0, 0, 0])
+    e = oracle.Oracle(cfg1)
+    e.reset(0)
+    buf = np.full((1, 8, 8), -1, np.int8)
+    buf[0, 0, :8] = [2, 0, 0, 0, 0, 0, 3, 0]                   # path 6, target 3: loss 3
+    e.set_state(buf, None, np.array([[1, 8]], np.int16), np.array([[0, 4]], np.int16))
+    _, r, _ = e.step(np.array([3], np.int32), want_obs=False)  # a door at column 4: path 4, loss 1
+    assert r[0] == 2.0
