@@ -66,6 +66,10 @@ extern "C" {
 #define PCGRL_OBS_STORE_CACHED 1 /* ordinary stores */
 #define PCGRL_OBS_STORE_STREAM 2 /* non-temporal stores */
 
+#define PCGRL_SPLIT_AUTO 0 /* decide from the number of wavefronts the batch needs */
+#define PCGRL_SPLIT_OFF 1  /* one wavefront per level group does the whole step */
+#define PCGRL_SPLIT_ON 2   /* pcgrl_step runs a metrics wavefront and an observation wavefront */
+
 #define PCGRL_MAX_METRICS 16
 #define PCGRL_MAX_TILES 8
 
@@ -94,6 +98,7 @@ typedef struct {
                            how many levels share one 64-lane wavefront (at most 64 / S, S = 16, 32
                            or 64 covering max_h and max_w; larger requests are rounded down) */
   int32_t obs_store_mode;  /* tuning only: PCGRL_OBS_STORE_* */
+  int32_t split_step;      /* tuning only: PCGRL_SPLIT_* */
   uint32_t init_cdf[PCGRL_MAX_TILES]; /* non-decreasing cumulative tile probabilities scaled by
                            2^32 (entry k = P(tile <= k)); the last tile takes the rest; all zero =
                            start from an all-empty map                      (Methods / Task) */

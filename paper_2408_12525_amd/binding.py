@@ -25,7 +25,7 @@ class PcgrlConfig(C.Structure):
         ("obs_w", C.c_int32), ("pad_mode", C.c_int32), ("pos_mode", C.c_int32),
         ("n_frozen", C.c_int32), ("max_steps", C.c_int32), ("max_changes", C.c_int32),
         ("autoreset", C.c_int32), ("regions_mode", C.c_int32), ("levels_per_wave", C.c_int32),
-        ("obs_store_mode", C.c_int32),
+        ("obs_store_mode", C.c_int32), ("split_step", C.c_int32),
         ("init_cdf", C.c_uint32 * MAX_TILES),
         ("weights", C.c_float * MAX_METRICS),
         ("target_lo", C.c_int32 * MAX_METRICS),

@@ -20,13 +20,15 @@ namespace pcgrl {
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMaxMetrics = 16;
-constexpr int kMaxBlock = 512;  // up to 8 independent wavefronts per workgroup
 
 enum : int { kBinary = 0, kMaze = 1, kDungeon = 2 };
 enum : int { kPadBorder = 0, kPadWall = 1 };
 enum : int { kPosScan = 0, kPosRandom = 1 };
 enum : int { kRegionsIncremental = 0, kRegionsRecount = 1 };
 enum : int { kInitGenerate = 1, kInitMetrics = 2, kInitObs = 4, kInitTargets = 8 };
+// step kernel variants: one step per launch; the same with the work of a wavefront split over
+// two (a metrics wavefront and an observation wavefront per workgroup); n steps per launch
+enum : int { kModeStep = 0, kModeSplit = 1, kModeRollout = 2 };
 
 // Per-environment scalars, 32 bytes, read and written as two 16-byte words.
 struct __attribute__((aligned(16))) EnvRec {
@@ -56,11 +58,9 @@ struct KArgs {
   int32_t max_h, max_w, min_h, min_w;
   int32_t obs_w, pad_mode, pos_mode, n_frozen, max_steps, max_changes, autoreset, regions_mode;
   int32_t env_obs_bytes;  // C * obs_w * obs_w
-  int32_t nwaves;         // wavefronts that have work
   int32_t envs_per_wave_log2;  // distinct levels per wavefront = 1 << this; at most 64 / S
   int32_t stream_obs;     // non-zero: write observations with non-temporal stores
   int32_t use_frozen;     // zero: no level of this context has a pinpoint cell
-  int32_t lds_words;      // LDS words of one wavefront's staging area
   int32_t flags;          // init kernel only
   int32_t rollout_steps;  // rollout kernel: steps per launch
   int32_t obs_slots;      // rollout kernel: step t writes observation slot t % obs_slots
@@ -658,12 +658,11 @@ template <int S> struct WaveMap {
   bool valid, primary;
   Slot sl;
   uint32_t* lds;
-  __device__ __forceinline__ bool init(const KArgs& a, const Lanes<S>& L, uint32_t* lds_all) {
+  // One workgroup per wavefront's worth of levels; the grid has exactly that many workgroups.
+  __device__ __forceinline__ void init(const KArgs& a, const Lanes<S>& L, uint32_t* lds_all) {
     constexpr int G = 64 / S;
-    const int wave_in_block = (int)(threadIdx.x >> 6);
-    wave = (int)blockIdx.x * (int)(blockDim.x >> 6) + wave_in_block;
-    if (wave >= a.nwaves) return false;  // whole wavefronts leave; no block-wide barrier is used
-    lds = lds_all + (size_t)wave_in_block * a.lds_words;
+    wave = (int)blockIdx.x;
+    lds = lds_all;
     const int lg = G == 1 ? 0 : a.envs_per_wave_log2;  // levels per wavefront = 1 << lg
     const int epw = 1 << lg;
     sl.copies = G >> lg;
@@ -675,7 +674,6 @@ template <int S> struct WaveMap {
     valid = env < a.B;
     primary = valid && sl.copy == 0;
     envl = valid ? env : env0;  // an index that is always safe to load from
-    return true;
   }
 };
 
@@ -694,13 +692,13 @@ __device__ __forceinline__ void observe(const KArgs& a, const Lanes<S>& L, const
 // loading the stored level, recomputing all metrics, restoring default targets, writing the
 // observation.
 template <int S, int PROBLEM>
-__global__ __launch_bounds__(kMaxBlock) void init_kernel(KArgs a) {
+__global__ __launch_bounds__(64) void init_kernel(KArgs a) {
   using W = typename RowWord<S>::T;
   using PR = Prob<PROBLEM>;
   extern __shared__ uint32_t lds_all[];
   Lanes<S> L;
   WaveMap<S> wm;
-  if (!wm.init(a, L, lds_all)) return;
+  wm.init(a, L, lds_all);
   W* planes = reinterpret_cast<W*>(a.planes);
   W* frozen = reinterpret_cast<W*>(a.frozen);
   const size_t ridx = (size_t)wm.envl * S + L.y;
@@ -757,14 +755,19 @@ __global__ __launch_bounds__(kMaxBlock) void init_kernel(KArgs a) {
 // One environment step of every level (pcgrl_step), or, with ROLL, `rollout_steps` consecutive
 // steps (pcgrl_rollout) during which the levels never leave the registers: per step only the
 // action is read and the observation, reward and done flag are written.
-template <int S, int PROBLEM, bool ROLL>
-__global__ __launch_bounds__(kMaxBlock) void step_kernel(KArgs a) {
+template <int S, int PROBLEM, int MODE>
+__global__ __launch_bounds__(MODE == kModeSplit ? 128 : 64) void step_kernel(KArgs a) {
   using W = typename RowWord<S>::T;
   using PR = Prob<PROBLEM>;
+  constexpr bool ROLL = MODE == kModeRollout, SPLIT = MODE == kModeSplit;
   extern __shared__ uint32_t lds_all[];
   Lanes<S> L;
   WaveMap<S> wm;
-  if (!wm.init(a, L, lds_all)) return;
+  wm.init(a, L, lds_all);
+  // SPLIT: the workgroup is two wavefronts on the same levels; wavefront 0 does the metrics, the
+  // reward and the state stores, wavefront 1 the observation; both load the same (old) state
+  const int role = SPLIT ? (int)(threadIdx.x >> 6) : 0;
+  if constexpr (SPLIT) wm.primary = wm.primary && role == 0;
   const bool valid = wm.valid;
   W* planes = reinterpret_cast<W*>(a.planes);
   W* frozen = reinterpret_cast<W*>(a.frozen);
@@ -777,7 +780,7 @@ __global__ __launch_bounds__(kMaxBlock) void step_kernel(KArgs a) {
   W fz = 0;  // pinpoint rows: resident only in a rollout; a single step keeps a flag with the cell
   if constexpr (ROLL) fz = frozen[ridx];
   EnvRec er = a.env[wm.envl];
-  int act = valid ? a.actions[wm.envl] : -1;
+  int act = a.actions[wm.envl];  // (lanes without a level of their own read a neighbour's and ignore it)
   int mo[PR::M];
   load_metrics<S, PROBLEM>(a.metrics + (size_t)wm.envl * kMaxMetrics, mo);
   constexpr int kTg = (PR::M + 3) / 4 * 4;
@@ -797,6 +800,8 @@ __global__ __launch_bounds__(kMaxBlock) void step_kernel(KArgs a) {
   for (int i = 0; i < kTg; ++i) asm volatile("" : "+v"(tg[i]));  // issue these loads here, not at their use
   int h = er.h, w = er.w, py = er.py, px = er.px;
   W inside = inside_row<W>(L.y, h, w);
+  // both wavefronts hold the old state in registers before either of them stores anything
+  if constexpr (SPLIT) __syncthreads();
   bool planes_dirty = false, fz_dirty = false;  // ROLL: what has to be written back at the end
   bool metrics_dirty = false, targets_dirty = false;
   W next_fz_row = 0;
@@ -806,7 +811,7 @@ __global__ __launch_bounds__(kMaxBlock) void step_kernel(KArgs a) {
     // the next step's action is requested now and used one iteration later
     int act_next = -1;
     if constexpr (ROLL) {
-      if (step + 1 < nsteps && valid) act_next = a.actions[(size_t)(step + 1) * a.B + wm.envl];
+      if (step + 1 < nsteps) act_next = a.actions[(size_t)(step + 1) * a.B + wm.envl];
     }
     uint8_t* obs = a.obs;
     if constexpr (ROLL) {
@@ -860,11 +865,18 @@ __global__ __launch_bounds__(kMaxBlock) void step_kernel(KArgs a) {
     if constexpr (!ROLL) {
       if (a.use_frozen) next_fz_row = frozen[(size_t)wm.envl * S + qy];
     }
-    // ---- observation around the new position.  It is issued before the metrics so that its
-    // stores drain while the floods run; a wavefront in which some level restarts writes it
-    // last, from the new episode's level.
+    // ---- observation around the new position.  It needs only the edited map and the new cell,
+    // so it is issued before the metrics and its stores drain while the floods run; a wavefront
+    // in which some level restarts writes it last, from the new episode's level.  (Letting odd
+    // wavefronts flood first and store later was measured and does not pay.)
     const bool any_restart = wave_any<S>(restart);
-    if (obs != nullptr && !any_restart) observe<S, PROBLEM>(a, L, wm, obs, p, inside, qy, qx);
+    const bool obs_late = any_restart;
+    if (obs != nullptr && !obs_late && (!SPLIT || role == 1))
+      observe<S, PROBLEM>(a, L, wm, obs, p, inside, qy, qx);
+    if constexpr (SPLIT) {
+      // the observation wavefront is done, unless a restart makes it wait for the new level
+      if (role == 1 && !any_restart) return;
+    }
 
     // ---- metrics, only where the edit modified the map (Methods / Task)
     int mn[PR::M];
@@ -981,7 +993,8 @@ __global__ __launch_bounds__(kMaxBlock) void step_kernel(KArgs a) {
       if (a.reward) a.reward[(size_t)step * a.B + wm.env] = reward;
       if (a.done) a.done[(size_t)step * a.B + wm.env] = done ? 1 : 0;
     }
-    if (obs != nullptr && any_restart) observe<S, PROBLEM>(a, L, wm, obs, p, inside, qy, qx);
+    if (obs != nullptr && obs_late && (!SPLIT || role == 1))
+      observe<S, PROBLEM>(a, L, wm, obs, p, inside, qy, qx);
 
     // ---- the new state becomes the current one
     py = qy;

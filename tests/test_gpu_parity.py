@@ -48,14 +48,17 @@ SMALL = [
 ]
 
 
-@pytest.mark.parametrize("lpw", [0, 2, 4], ids=["auto", "lpw2", "lpw4"])
+@pytest.mark.parametrize("lpw,split", [(0, 0), (2, 1), (4, 2), (1, 1)],
+                         ids=["auto", "lpw2-unsplit", "lpw4-split", "lpw1-unsplit"])
 @pytest.mark.parametrize("label,cfg,steps,extra", SMALL, ids=[s[0] for s in SMALL])
-def test_small_configs_every_step(label, cfg, steps, extra, lpw):
-    """lpw = levels packed into one wavefront: automatic (1 at these batch sizes), 2, and as many
-    as the size class takes."""
-    if lpw and max(cfg["max_h"], cfg["max_w"]) > 32:
+def test_small_configs_every_step(label, cfg, steps, extra, lpw, split):
+    """lpw = levels packed into one wavefront (automatic = 1 at these batch sizes, 2, as many as
+    the size class takes); split = one wavefront per level group, or a metrics wavefront and an
+    observation wavefront (automatic = split at these batch sizes)."""
+    if lpw > 1 and max(cfg["max_h"], cfg["max_w"]) > 32:
         pytest.skip("a 64-row level fills the wavefront")
-    run_parity(dict(cfg, levels_per_wave=lpw), steps, label=f"{label} lpw={lpw}", **extra)
+    run_parity(dict(cfg, levels_per_wave=lpw, split_step=split), steps,
+               label=f"{label} lpw={lpw} split={split}", **extra)
 
 
 def test_control_targets_and_fractional_weights():
@@ -147,7 +150,8 @@ def test_results_do_not_depend_on_batch_partition():
 def test_argument_errors_are_reported_not_raised_by_the_gpu():
     bad = wl.workload("maze16", batch=4)
     for field, val in (("obs_w", 64), ("max_h", 65), ("batch", 0), ("problem", 3), ("n_frozen", 9),
-                       ("min_h", 17), ("max_steps", 0), ("pad_mode", 2), ("levels_per_wave", 5)):
+                       ("min_h", 17), ("max_steps", 0), ("pad_mode", 2), ("levels_per_wave", 5),
+                       ("split_step", 3), ("obs_store_mode", 3)):
         with pytest.raises(binding.PcgrlError):
             binding.Pcgrl(dict(bad, **{field: val}), 0)
     env = binding.Pcgrl(bad, 0)
