@@ -404,3 +404,51 @@ def test_largest_batch_spot_check():
     t = g["tiles"][tidx].cpu().numpy()
     assert (o[np.arange(len(idx)), t[np.arange(len(idx)), pos[:, 0], pos[:, 1]], 15, 15] == 1).all()
     gpu.close()
+
+
+LONG = [
+    ("maze16", wl.workload("maze16", batch=96, max_steps=3000), 4000),
+    ("binary16", wl.workload("binary16", batch=64, max_steps=1000), 2500),
+    ("dungeon32", wl.workload("dungeon32", batch=48, max_steps=1500), 2000),
+    ("binary32 rand", wl.workload("binary32_rand_ow15", batch=48, max_steps=1000), 2000),
+    ("maze64", wl.workload("maze64", batch=12, max_steps=1000), 1500),
+    ("binary64 dense", wl.make_config(wl.BINARY, 8, 64, 31, max_steps=2000, probs=[.62, .38]), 1500),
+]
+
+
+@pytest.mark.parametrize("label,cfg,steps", LONG, ids=[l[0] for l in LONG])
+def test_long_runs_do_not_drift(label, cfg, steps):
+    """Thousands of steps in a row (the map drifts from its initial tile mix towards uniform, the
+    incrementally maintained region and tile counts never get a fresh start inside an episode):
+    rewards, done flags and metrics every step, observations and state now and then."""
+    print(f"[long] {label} steps={steps}", flush=True)
+    dev = torch.device("cuda", 0)
+    B = cfg["batch"]
+    gpu, cpu = binding.Pcgrl(cfg, 0), oracle.Oracle(cfg)
+    obs = gpu.new_obs()
+    gpu.pcgrl_reset(77, obs)
+    cpu.reset(77, want_obs=False)
+    acts_np = wl.random_actions(cfg, 78, steps)
+    acts = torch.from_numpy(acts_np).to(dev)
+    chunk = 50
+    rew = torch.empty((chunk, B), dtype=torch.float32, device=dev)
+    done = torch.empty((chunk, B), dtype=torch.uint8, device=dev)
+    met = torch.empty((chunk, B, gpu.M), dtype=torch.int32, device=dev)
+    for t0 in range(0, steps, chunk):
+        n = min(chunk, steps - t0)
+        for k in range(n):
+            gpu.pcgrl_step(acts[t0 + k], obs, rew[k], done[k])
+            gpu.pcgrl_metrics(met[k])
+        g_r, g_d, g_m = rew.cpu().numpy(), done.cpu().numpy(), met.cpu().numpy()
+        for k in range(n):
+            last = k == n - 1
+            o, r, d = cpu.step(acts_np[t0 + k], want_obs=last)
+            ctx = f"step {t0 + k}"
+            assert np.array_equal(g_r[k], r), "reward " + ctx
+            assert np.array_equal(g_d[k], d), "done " + ctx
+            assert np.array_equal(g_m[k], cpu.metrics()), "metrics " + ctx
+        assert_same("obs", obs, o, f"step {t0 + n - 1}")
+        if (t0 // chunk) % 8 == 0:
+            compare_state(gpu, cpu, f"step {t0 + n - 1}")
+    compare_state(gpu, cpu, "end")
+    gpu.close()
