@@ -70,6 +70,11 @@ extern "C" {
 #define PCGRL_SPLIT_OFF 1  /* one wavefront per level group does the whole step */
 #define PCGRL_SPLIT_ON 2   /* pcgrl_step runs a metrics wavefront and an observation wavefront */
 
+#define PCGRL_OBS_ONEHOT_U8 0 /* uint8 [batch][C][obs_w][obs_w], one byte per one-hot cell */
+#define PCGRL_OBS_PACKED 1    /* the same cells as bits: uint8 [batch][ceil(C*obs_w*obs_w / 8)], cell j of
+                                 a level (j = (c*obs_w + i)*obs_w + k) is bit j%8 of its byte j/8;
+                                 eight times fewer bytes for a consumer that unpacks on the fly */
+
 #define PCGRL_MAX_METRICS 16
 #define PCGRL_MAX_TILES 8
 
@@ -99,6 +104,7 @@ typedef struct {
                            or 64 covering max_h and max_w; larger requests are rounded down) */
   int32_t obs_store_mode;  /* tuning only: PCGRL_OBS_STORE_* */
   int32_t split_step;      /* tuning only: PCGRL_SPLIT_* */
+  int32_t obs_format;      /* PCGRL_OBS_*: every `obs` argument below has this format */
   uint32_t init_cdf[PCGRL_MAX_TILES]; /* non-decreasing cumulative tile probabilities scaled by
                            2^32 (entry k = P(tile <= k)); the last tile takes the rest; all zero =
                            start from an all-empty map                      (Methods / Task) */
@@ -198,6 +204,7 @@ int pcgrl_get_targets(pcgrl_ctx* ctx, int32_t* out, void* stream);
 
 /* Shape queries (host side, no GPU work).  out: host pointer to 4 ints = batch, C, obs_w, obs_w. */
 int pcgrl_obs_shape(const pcgrl_ctx* ctx, int32_t out[4]);
+int64_t pcgrl_obs_bytes(const pcgrl_ctx* ctx); /* bytes of one level's observation in obs_format */
 int pcgrl_num_metrics(const pcgrl_ctx* ctx);
 int pcgrl_num_tiles(const pcgrl_ctx* ctx);
 

@@ -26,6 +26,7 @@ class PcgrlConfig(C.Structure):
         ("n_frozen", C.c_int32), ("max_steps", C.c_int32), ("max_changes", C.c_int32),
         ("autoreset", C.c_int32), ("regions_mode", C.c_int32), ("levels_per_wave", C.c_int32),
         ("obs_store_mode", C.c_int32), ("split_step", C.c_int32),
+        ("obs_format", C.c_int32),
         ("init_cdf", C.c_uint32 * MAX_TILES),
         ("weights", C.c_float * MAX_METRICS),
         ("target_lo", C.c_int32 * MAX_METRICS),
@@ -41,7 +42,7 @@ EXPORTS = [
     "pcgrl_config_default", "pcgrl_create", "pcgrl_destroy", "pcgrl_reset", "pcgrl_step", "pcgrl_rollout",
     "pcgrl_metrics", "pcgrl_observe", "pcgrl_get_state", "pcgrl_set_state", "pcgrl_set_targets",
     "pcgrl_get_targets",
-    "pcgrl_obs_shape", "pcgrl_num_metrics", "pcgrl_num_tiles", "pcgrl_bad_action_count",
+    "pcgrl_obs_shape", "pcgrl_obs_bytes", "pcgrl_num_metrics", "pcgrl_num_tiles", "pcgrl_bad_action_count",
     "pcgrl_selftest", "pcgrl_strerror",
 ]
 
@@ -80,6 +81,8 @@ def load():
     L.pcgrl_set_targets.argtypes = [p, p, p]
     L.pcgrl_get_targets.argtypes = [p, p, p]
     L.pcgrl_obs_shape.argtypes = [p, C.POINTER(i32 * 4)]
+    L.pcgrl_obs_bytes.argtypes = [p]
+    L.pcgrl_obs_bytes.restype = C.c_int64
     L.pcgrl_num_metrics.argtypes = [p]
     L.pcgrl_num_tiles.argtypes = [p]
     L.pcgrl_bad_action_count.argtypes = [p, C.POINTER(u64), p]
@@ -135,6 +138,8 @@ class Pcgrl:
         shp = (C.c_int32 * 4)()
         _check(self.L.pcgrl_obs_shape(self.h, C.byref(shp)), "pcgrl_obs_shape")
         self.obs_shape = tuple(shp)
+        if self.cfg.obs_format != 0:     # bit-packed: one flat byte row per level
+            self.obs_shape = (shp[0], int(self.L.pcgrl_obs_bytes(self.h)))
         self.B = self.cfg.batch
         self.M = self.L.pcgrl_num_metrics(self.h)
         self.K = self.L.pcgrl_num_tiles(self.h)
@@ -191,7 +196,7 @@ class Pcgrl:
         slots = 1
         o = None
         if obs is not None:
-            slots = obs.shape[0] if obs.dim() == 5 else 0
+            slots = obs.shape[0] if obs.dim() == len(self.obs_shape) + 1 else 0
             o = self._dev(obs, torch.uint8, (slots,) + tuple(self.obs_shape), "obs")
         r = self._dev(reward, torch.float32, (T, self.B), "reward", optional=True)
         d = self._dev(done, torch.uint8, (T, self.B), "done", optional=True)

@@ -19,6 +19,7 @@ struct pcgrl_ctx {
   size_t word_bytes;
   size_t lds_bytes;  // per wavefront
   int split;         // pcgrl_step with an observation uses the two-wavefront kernel
+  size_t obs_bytes;  // bytes of one level's observation in the chosen format
   KArgs base;  // device pointers and configuration, copied into every launch
   void* d_planes;
   void* d_frozen;
@@ -60,6 +61,7 @@ int check_config(const pcgrl_config* c) {
   if (c->levels_per_wave < 0 || c->levels_per_wave > 4) return PCGRL_E_CONFIG;
   if (c->obs_store_mode < 0 || c->obs_store_mode > 2) return PCGRL_E_CONFIG;
   if (c->split_step < 0 || c->split_step > 2) return PCGRL_E_CONFIG;
+  if (c->obs_format != PCGRL_OBS_ONEHOT_U8 && c->obs_format != PCGRL_OBS_PACKED) return PCGRL_E_CONFIG;
   for (int j = 0; j < 8; ++j)
     if (c->pinpoint_tile[j] < -1 || c->pinpoint_tile[j] >= tiles_of(c->problem)) return PCGRL_E_CONFIG;
   for (int i = 0; i < metrics_of(c->problem); ++i)
@@ -214,8 +216,10 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   ctx->nwaves = (cfg->batch + ctx->epw - 1) / ctx->epw;
   ctx->B_pad = ctx->nwaves * ctx->epw;
   ctx->word_bytes = ctx->S == 64 ? 8 : 4;
-  const size_t E = (size_t)ctx->C * cfg->obs_w * cfg->obs_w;
-  ctx->lds_bytes = ((15 + (size_t)ctx->epw * E + 31) / 32 + 2) * 4;
+  const size_t E1 = (size_t)ctx->C * cfg->obs_w * cfg->obs_w;  // one-hot cells of one observation
+  const size_t E = cfg->obs_format == PCGRL_OBS_PACKED ? (E1 + 7) / 8 : E1;  // its bytes
+  ctx->obs_bytes = E;
+  ctx->lds_bytes = ((8 * 15 + (size_t)ctx->epw * (E1 + 8) + 31) / 32 + 6) * 4;
   if (ctx->lds_bytes > 64 * 1024) {
     delete ctx;
     return PCGRL_E_CONFIG;
@@ -269,6 +273,7 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   a.autoreset = cfg->autoreset;
   a.regions_mode = cfg->regions_mode;
   a.env_obs_bytes = (int32_t)E;
+  a.obs_packed = cfg->obs_format == PCGRL_OBS_PACKED ? 1 : 0;
   a.envs_per_wave_log2 = ctx->epw == 4 ? 2 : ctx->epw == 2 ? 1 : 0;
   a.use_frozen = cfg->n_frozen > 0 ? 1 : 0;
   // How the observation is stored (measured on MI355X, see the design notes): streaming stores
@@ -428,6 +433,8 @@ int pcgrl_obs_shape(const pcgrl_ctx* ctx, int32_t out[4]) {
   out[3] = ctx->cfg.obs_w;
   return PCGRL_OK;
 }
+
+int64_t pcgrl_obs_bytes(const pcgrl_ctx* ctx) { return ctx ? (int64_t)ctx->obs_bytes : PCGRL_E_NULL; }
 
 int pcgrl_num_metrics(const pcgrl_ctx* ctx) { return ctx ? ctx->M : PCGRL_E_NULL; }
 int pcgrl_num_tiles(const pcgrl_ctx* ctx) { return ctx ? ctx->K : PCGRL_E_NULL; }

@@ -57,7 +57,8 @@ struct KArgs {
   int32_t B, plane_stride;
   int32_t max_h, max_w, min_h, min_w;
   int32_t obs_w, pad_mode, pos_mode, n_frozen, max_steps, max_changes, autoreset, regions_mode;
-  int32_t env_obs_bytes;  // C * obs_w * obs_w
+  int32_t env_obs_bytes;  // bytes of one level's observation: C * obs_w * obs_w, or an eighth (rounded up) when packed
+  int32_t obs_packed;     // non-zero: bit-packed observation format
   int32_t envs_per_wave_log2;  // distinct levels per wavefront = 1 << this; at most 64 / S
   int32_t stream_obs;     // non-zero: write observations with non-temporal stores
   int32_t use_frozen;     // zero: no level of this context has a pinpoint cell
@@ -534,9 +535,13 @@ __device__ __forceinline__ void write_obs(const KArgs& a, const Lanes<S>& L, con
   using BW = typename std::conditional<WIDE, uint64_t, uint32_t>::type;  // one window row
   const int ow = a.obs_w, r = ow >> 1;
   const int C = PR::K + (a.pad_mode == kPadBorder ? 1 : 0);
-  const int E = a.env_obs_bytes;
-  uint8_t* region = obs + (size_t)env0 * (size_t)E;
-  const int d = (int)((uintptr_t)region & 15u);
+  // One level's part of the stream is E bits long; its output is E bytes (one byte per bit) or,
+  // bit-packed, E / 8 bytes.  dbytes = distance of the region from a 16-byte boundary.
+  const bool packed = a.obs_packed != 0;
+  const int E = packed ? a.env_obs_bytes * 8 : a.env_obs_bytes;
+  uint8_t* region = obs + (size_t)env0 * (size_t)a.env_obs_bytes;
+  const int dbytes = (int)((uintptr_t)region & 15u);
+  const int d = packed ? dbytes * 8 : dbytes;
   const int total = d + nvalid * E;  // stream length in bits
   const int nwords = (total + 31) >> 5;
   for (int i = L.lane; i < nwords; i += 64) lds[i] = 0;
@@ -587,7 +592,23 @@ __device__ __forceinline__ void write_obs(const KArgs& a, const Lanes<S>& L, con
   }
   lds_sync();
 
-  uint8_t* base = region - d;  // 16-byte aligned
+  uint8_t* base = region - dbytes;  // 16-byte aligned
+  if (packed) {
+    // bit-packed format: the stream itself is the output, 128 bits per aligned 16-byte chunk
+    const int total_bytes = total >> 3;
+    const int p_lo = (dbytes + 15) >> 4, p_hi = total_bytes >> 4;
+    const uint4* lds128 = reinterpret_cast<const uint4*>(lds);
+    for (int q = p_lo + L.lane; q < p_hi; q += 64)
+      *reinterpret_cast<uint4*>(base + ((uint32_t)q << 4)) = lds128[q];
+    const int t = L.lane & 15;
+    const bool is_tail = L.lane >= 16;
+    const int q = is_tail ? p_hi : 0;
+    const bool want = L.lane < 32 && (is_tail ? ((total_bytes & 15) != 0 && (p_hi > 0 || dbytes == 0)) : dbytes > 0);
+    const int pos = (q << 4) + t;
+    if (want && pos >= dbytes && pos < total_bytes)
+      base[pos] = reinterpret_cast<const uint8_t*>(lds)[pos];
+    return;
+  }
   const uint16_t* lds16 = reinterpret_cast<const uint16_t*>(lds);
   auto widen = [&](uint32_t b) {
     uint4 v;

@@ -16,6 +16,14 @@ def assert_same(name, got, want, ctx):
                              f"gpu={got[first] if first else None} oracle={want[first] if first else None}")
 
 
+def expected_obs(cfg, onehot):
+    """The oracle's one-hot bytes in the format the GPU context was asked for (bit-packed: cell j
+    of a level becomes bit j % 8 of byte j // 8 -- numpy's little-endian packbits)."""
+    if cfg.get("obs_format", 0):
+        return np.packbits(onehot.reshape(onehot.shape[0], -1), axis=1, bitorder="little")
+    return onehot
+
+
 def run_parity(cfg, steps, seed=1, aseed=2, bad_fraction=0.0, check_every=1, state_every=25,
                env_slice=None, targets=None, label=""):
     """Steps both implementations `steps` times.  Observations, rewards, done flags and metrics
@@ -36,7 +44,7 @@ def run_parity(cfg, steps, seed=1, aseed=2, bad_fraction=0.0, check_every=1, sta
     if targets is not None:
         gpu.pcgrl_set_targets(torch.from_numpy(targets).to(dev))
         cpu.set_targets(targets)
-    assert_same("obs", obs[sl], want_obs[sl], "after reset")
+    assert_same("obs", obs[sl], expected_obs(cfg, want_obs)[sl], "after reset")
     assert_same("metrics", gpu.pcgrl_metrics()[sl], cpu.metrics()[sl], "after reset")
     compare_state(gpu, cpu, "after reset")
     acts = wl.random_actions(cfg, aseed, steps, bad_fraction)
@@ -53,7 +61,7 @@ def run_parity(cfg, steps, seed=1, aseed=2, bad_fraction=0.0, check_every=1, sta
             bad = np.flatnonzero(~(np.abs(g[sl] - r[sl]) <= 1e-6))
             assert len(bad) == 0, (f"reward differs {ctx} in {len(bad)} envs; first env {bad[0]}: "
                                    f"gpu={g[sl][bad[0]]} oracle={r[sl][bad[0]]}")
-            assert_same("obs", obs[sl], o[sl], ctx)
+            assert_same("obs", obs[sl], expected_obs(cfg, o)[sl], ctx)
         if t % state_every == 0 or t == steps - 1:
             compare_state(gpu, cpu, f"at step {t}")
     if bad_fraction > 0:

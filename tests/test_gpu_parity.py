@@ -5,7 +5,7 @@ import torch
 
 import levels
 import oracle
-from parity import assert_same, compare_state, run_parity
+from parity import assert_same, compare_state, expected_obs, run_parity
 from paper_2408_12525_amd import binding, workloads as wl
 
 pytestmark = pytest.mark.gpu
@@ -39,6 +39,10 @@ SMALL = [
     ("binary64 sparse walls", wl.make_config(wl.BINARY, 6, 64, 31, max_steps=90, probs=[.8, .2]), 120, {}),
     ("dungeon64 ow1", wl.make_config(wl.DUNGEON, 4, 40, 1, max_w=64, max_steps=90), 100, {}),
     ("batch of one", wl.make_config(wl.MAZE, 1, 16, 31, max_steps=30), 70, {}),
+    ("maze16 bit-packed obs", wl.workload("maze16", batch=77, max_steps=40, obs_format=1), 100, {}),
+    ("binary32 rand ow63 bit-packed", wl.workload("binary32_rand_ow63", batch=13, max_steps=30, obs_format=1), 70, {}),
+    ("dungeon64 ow5 bit-packed", wl.make_config(wl.DUNGEON, 7, 64, 5, min_size=20, max_steps=30, obs_format=1), 70, {}),
+    ("binary16 ow1 bit-packed", wl.make_config(wl.BINARY, 40, 16, 1, max_steps=30, obs_format=1, pad_mode=wl.PAD_WALL), 50, {}),
     ("maze16 pinpointed player and door", wl.workload("maze16_pinpoint", batch=90, max_steps=33), 120, {}),
     ("dungeon16 control targets", wl.workload("dungeon16_ctrl", batch=50, max_steps=27), 120, {}),
     ("maze32 pinpoints + control, scan", wl.make_config(wl.MAZE, 30, 32, 16, min_size=3, probs="empty", n_frozen=4,
@@ -224,6 +228,7 @@ ROLLOUTS = [
     ("binary64 budget", wl.make_config(wl.BINARY, 5, 64, 63, min_size=40, n_frozen=5, max_changes=9, max_steps=100), 60, 3),
     ("dungeon16 control targets", wl.workload("dungeon16_ctrl", batch=40, max_steps=13), 60, 2),
     ("maze16 pinpointed", wl.workload("maze16_pinpoint", batch=40, max_steps=19), 60, 60),
+    ("maze16 bit-packed", wl.workload("maze16", batch=40, max_steps=19, obs_format=1), 40, 5),
 ]
 
 
@@ -251,7 +256,7 @@ def test_rollout_equals_the_same_steps_one_by_one(label, cfg, T, slots):
     d1 = torch.empty(B, dtype=torch.uint8, device=dev)
     for t in range(T):
         o, r, d = cpu.step(acts_np[t])
-        want_obs[t % slots] = o
+        want_obs[t % slots] = expected_obs(cfg, o)
         assert np.array_equal(rew[t].cpu().numpy(), r), f"reward step {t}"
         assert np.array_equal(done[t].cpu().numpy(), d), f"done step {t}"
         single.pcgrl_step(acts[t], o1, r1, d1)
@@ -271,7 +276,7 @@ def test_rollout_equals_the_same_steps_one_by_one(label, cfg, T, slots):
     a3 = wl.random_actions(cfg, 10, 1)[0]
     roll.pcgrl_step(torch.from_numpy(a3).to(dev), o1, r1, d1)
     o, r, d = cpu.step(a3)
-    assert_same("obs", o1, o, "step after rollout")
+    assert_same("obs", o1, expected_obs(cfg, o), "step after rollout")
     assert np.array_equal(r1.cpu().numpy(), r)
     assert_same("metrics", roll.pcgrl_metrics(), cpu.metrics(), "step after rollout")
     for e in (roll, single):
