@@ -120,6 +120,8 @@ typedef struct {
                            the user or a curriculum varies target path length or nearest enemy) */
   int32_t ctrl_lo[PCGRL_MAX_METRICS];
   int32_t ctrl_hi[PCGRL_MAX_METRICS];
+  int32_t obs_frozen_channel; /* non-zero: the observation gets one more (last) channel that is 1 on
+                           the pinpoint cells in view, so that the agent can see what it cannot edit */
 } pcgrl_config;
 
 /* Fills *cfg with this library's defaults for a problem: fixed 16x16 map, window 31, border
@@ -149,7 +151,8 @@ int pcgrl_reset(pcgrl_ctx* ctx, uint64_t seed, uint8_t* obs, void* stream);
  *            0..K-1 is a no-op edit (counted, see pcgrl_bad_action_count); so is writing the tile
  *            already there or writing to a frozen cell.
  *   obs    : device, uint8 [batch][C][obs_w][obs_w], planar one-hot window centred on the agent's
- *            NEW cell; C = K, plus 1 under PCGRL_PAD_BORDER.  May be NULL.
+ *            NEW cell; C = K, plus 1 under PCGRL_PAD_BORDER, plus 1 with obs_frozen_channel
+ *            (bit-packed under PCGRL_OBS_PACKED).  May be NULL.
  *   reward : device, float32 [batch]: sum over metrics, in index order, of
  *            weight * (loss before - loss after); exactly 0 when the edit was a no-op.
  *   done   : device, uint8 [batch].

@@ -39,6 +39,7 @@ class OrcConfig(C.Structure):
         ("ctrl_mask", C.c_uint32),
         ("ctrl_lo", C.c_int32 * MAX_METRICS),
         ("ctrl_hi", C.c_int32 * MAX_METRICS),
+        ("obs_frozen_channel", C.c_int32),
     ]
 
 

@@ -69,7 +69,8 @@ int orc_num_metrics(int problem) {
 }
 
 int orc_num_channels(const orc_config* cfg) {
-  return orc_num_tiles(cfg->problem) + (cfg->pad_mode == ORC_PAD_BORDER ? 1 : 0);
+  return orc_num_tiles(cfg->problem) + (cfg->pad_mode == ORC_PAD_BORDER ? 1 : 0) +
+         (cfg->obs_frozen_channel ? 1 : 0);
 }
 
 /* --------------------------------------------------- counter-based numbers */
@@ -406,8 +407,12 @@ static void env_observe(const orc_ctx* ctx, const orc_env* e, uint8_t* obs) {
     for (int j = 0; j < ow; ++j) {
       int p = e->py - r + i, q = e->px - r + j;
       int ch = pad;
-      if (p >= 0 && p < e->h && q >= 0 && q < e->w) ch = e->tiles[p * c->max_w + q];
+      int in = p >= 0 && p < e->h && q >= 0 && q < e->w;
+      if (in) ch = e->tiles[p * c->max_w + q];
       obs[((size_t)ch * ow + i) * ow + j] = 1;
+      /* optional last channel: which cells in view the agent cannot change (pinpoints) */
+      if (c->obs_frozen_channel && in && e->frozen[p * c->max_w + q])
+        obs[((size_t)(ctx->C - 1) * ow + i) * ow + j] = 1;
     }
 }
 

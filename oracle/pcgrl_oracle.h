@@ -64,6 +64,7 @@ typedef struct {
   uint32_t ctrl_mask;       /* bit i: metric i's target is drawn anew every episode ... */
   int32_t ctrl_lo[ORC_MAX_METRICS]; /* ... uniformly from [ctrl_lo[i], ctrl_hi[i]] and used as an */
   int32_t ctrl_hi[ORC_MAX_METRICS]; /* exact target (lo = hi = the drawn value) */
+  int32_t obs_frozen_channel; /* non-zero: one more (last) channel marks the pinpoint cells in view */
 } orc_config;
 
 typedef struct orc_ctx orc_ctx;

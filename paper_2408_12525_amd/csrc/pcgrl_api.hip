@@ -203,7 +203,7 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   ctx->K = tiles_of(cfg->problem);
   ctx->P = planes_of(cfg->problem);
   ctx->M = metrics_of(cfg->problem);
-  ctx->C = ctx->K + (cfg->pad_mode == PCGRL_PAD_BORDER ? 1 : 0);
+  ctx->C = ctx->K + (cfg->pad_mode == PCGRL_PAD_BORDER ? 1 : 0) + (cfg->obs_frozen_channel ? 1 : 0);
   // Levels per wavefront: all G groups when the batch alone fills the machine; fewer (the spare
   // groups then hold copies that share the observation work) when that is what it takes to have
   // about two wavefronts on each of the 1024 SIMDs (measured optimum).
@@ -274,6 +274,7 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   a.regions_mode = cfg->regions_mode;
   a.env_obs_bytes = (int32_t)E;
   a.obs_packed = cfg->obs_format == PCGRL_OBS_PACKED ? 1 : 0;
+  a.obs_frozen_channel = cfg->obs_frozen_channel ? 1 : 0;
   a.envs_per_wave_log2 = ctx->epw == 4 ? 2 : ctx->epw == 2 ? 1 : 0;
   a.use_frozen = cfg->n_frozen > 0 ? 1 : 0;
   // How the observation is stored (measured on MI355X, see the design notes): streaming stores

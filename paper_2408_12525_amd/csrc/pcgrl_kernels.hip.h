@@ -59,6 +59,7 @@ struct KArgs {
   int32_t obs_w, pad_mode, pos_mode, n_frozen, max_steps, max_changes, autoreset, regions_mode;
   int32_t env_obs_bytes;  // bytes of one level's observation: C * obs_w * obs_w, or an eighth (rounded up) when packed
   int32_t obs_packed;     // non-zero: bit-packed observation format
+  int32_t obs_frozen_channel;  // non-zero: a last channel marks the pinpoint cells in view
   int32_t envs_per_wave_log2;  // distinct levels per wavefront = 1 << this; at most 64 / S
   int32_t stream_obs;     // non-zero: write observations with non-temporal stores
   int32_t use_frozen;     // zero: no level of this context has a pinpoint cell
@@ -528,13 +529,14 @@ template <int S, int PROBLEM, bool WIDE>
 __device__ __forceinline__ void write_obs(const KArgs& a, const Lanes<S>& L, const Slot& sl,
                                           uint32_t* lds, uint8_t* obs,
                                           const typename RowWord<S>::T (&p)[Prob<PROBLEM>::P],
-                                          typename RowWord<S>::T inside, int qy, int qx, int env0,
-                                          int nvalid) {
+                                          typename RowWord<S>::T fz, typename RowWord<S>::T inside,
+                                          int qy, int qx, int env0, int nvalid) {
   using W = typename RowWord<S>::T;
   using PR = Prob<PROBLEM>;
   using BW = typename std::conditional<WIDE, uint64_t, uint32_t>::type;  // one window row
   const int ow = a.obs_w, r = ow >> 1;
-  const int C = PR::K + (a.pad_mode == kPadBorder ? 1 : 0);
+  const int Cfz = PR::K + (a.pad_mode == kPadBorder ? 1 : 0);  // index of the pinpoint channel, if any
+  const int C = Cfz + (a.obs_frozen_channel ? 1 : 0);
   // One level's part of the stream is E bits long; its output is E bytes (one byte per bit) or,
   // bit-packed, E / 8 bytes.  dbytes = distance of the region from a 16-byte boundary.
   const bool packed = a.obs_packed != 0;
@@ -560,6 +562,7 @@ __device__ __forceinline__ void write_obs(const KArgs& a, const Lanes<S>& L, con
 #pragma unroll
     for (int k = 0; k < PR::P; ++k) wp[k] = window(p[k]);
     const BW win_in = window(inside);
+    const BW win_fz = window(fz) & win_in;
     const BW out_win = (BW)~win_in & owmask;  // window cells outside the map's columns
     const int padc = a.pad_mode == kPadBorder ? PR::K : 1;
     const int cstride = ow * ow;
@@ -573,6 +576,7 @@ __device__ __forceinline__ void write_obs(const KArgs& a, const Lanes<S>& L, con
 #pragma unroll
         for (int k = 0; k < PR::P; ++k) bits &= ((c >> k) & 1) ? wp[k] : (BW)~wp[k];
         bits |= c == padc ? pad_bits : (BW)0;
+        if (c == Cfz) bits = real ? win_fz : (BW)0;
         if (bits != 0) {
           const int w0 = off >> 5, sh = off & 31;
           if constexpr (WIDE) {
@@ -702,11 +706,12 @@ template <int S, int PROBLEM>
 __device__ __forceinline__ void observe(const KArgs& a, const Lanes<S>& L, const WaveMap<S>& wm,
                                         uint8_t* obs,
                                         const typename RowWord<S>::T (&p)[Prob<PROBLEM>::P],
-                                        typename RowWord<S>::T inside, int qy, int qx) {
+                                        typename RowWord<S>::T fz, typename RowWord<S>::T inside,
+                                        int qy, int qx) {
   if (a.obs_w > 32)
-    write_obs<S, PROBLEM, true>(a, L, wm.sl, wm.lds, obs, p, inside, qy, qx, wm.env0, wm.nvalid);
+    write_obs<S, PROBLEM, true>(a, L, wm.sl, wm.lds, obs, p, fz, inside, qy, qx, wm.env0, wm.nvalid);
   else
-    write_obs<S, PROBLEM, false>(a, L, wm.sl, wm.lds, obs, p, inside, qy, qx, wm.env0, wm.nvalid);
+    write_obs<S, PROBLEM, false>(a, L, wm.sl, wm.lds, obs, p, fz, inside, qy, qx, wm.env0, wm.nvalid);
 }
 
 // Reset / refresh / observe: flags choose between generating a fresh episode 0 from the seed or
@@ -753,6 +758,8 @@ __global__ __launch_bounds__(64) void init_kernel(KArgs a) {
     px = er.px;
 #pragma unroll
     for (int i = 0; i < PR::P; ++i) p[i] = planes[(size_t)i * a.plane_stride + ridx];
+    fz = 0;
+    if ((a.flags & kInitObs) && a.obs_frozen_channel) fz = frozen[ridx];
     if (a.flags & kInitMetrics) {  // a level was installed: its pinpoint flag has to be refreshed
       fz = frozen[ridx];
       er.cell_frozen = L.gany(L.y == py && ((fz >> px) & 1)) ? 1u : 0u;
@@ -770,7 +777,7 @@ __global__ __launch_bounds__(64) void init_kernel(KArgs a) {
     if ((a.ctrl_mask >> L.y) & 1u) t = control_target(a, er.key, L.y);
     a.targets[(size_t)wm.env * kMaxMetrics + L.y] = t;
   }
-  if ((a.flags & kInitObs) && a.obs != nullptr) observe<S, PROBLEM>(a, L, wm, a.obs, p, inside, py, px);
+  if ((a.flags & kInitObs) && a.obs != nullptr) observe<S, PROBLEM>(a, L, wm, a.obs, p, fz, inside, py, px);
 }
 
 // One environment step of every level (pcgrl_step), or, with ROLL, `rollout_steps` consecutive
@@ -799,7 +806,7 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 128 : 64) void step_kernel(KAr
 #pragma unroll
   for (int i = 0; i < PR::P; ++i) p[i] = planes[(size_t)i * a.plane_stride + ridx];
   W fz = 0;  // pinpoint rows: resident only in a rollout; a single step keeps a flag with the cell
-  if constexpr (ROLL) fz = frozen[ridx];
+  if (ROLL || (a.obs_frozen_channel && a.use_frozen)) fz = frozen[ridx];
   EnvRec er = a.env[wm.envl];
   int act = a.actions[wm.envl];  // (lanes without a level of their own read a neighbour's and ignore it)
   int mo[PR::M];
@@ -893,7 +900,7 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 128 : 64) void step_kernel(KAr
     const bool any_restart = wave_any<S>(restart);
     const bool obs_late = any_restart;
     if (obs != nullptr && !obs_late && (!SPLIT || role == 1))
-      observe<S, PROBLEM>(a, L, wm, obs, p, inside, qy, qx);
+      observe<S, PROBLEM>(a, L, wm, obs, p, fz, inside, qy, qx);
     if constexpr (SPLIT) {
       // the observation wavefront is done, unless a restart makes it wait for the new level
       if (role == 1 && !any_restart) return;
@@ -980,9 +987,8 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 128 : 64) void step_kernel(KAr
             if (wm.primary) planes[(size_t)i * a.plane_stride + ridx] = np[i];
           }
         }
-        if constexpr (ROLL) {
-          fz = nfz;
-        } else {
+        fz = nfz;
+        if constexpr (!ROLL) {
           if (wm.primary) frozen[ridx] = nfz;
           next_fz_row = L.gread(nfz, npy);
         }
@@ -1015,7 +1021,7 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 128 : 64) void step_kernel(KAr
       if (a.done) a.done[(size_t)step * a.B + wm.env] = done ? 1 : 0;
     }
     if (obs != nullptr && obs_late && (!SPLIT || role == 1))
-      observe<S, PROBLEM>(a, L, wm, obs, p, inside, qy, qx);
+      observe<S, PROBLEM>(a, L, wm, obs, p, fz, inside, qy, qx);
 
     // ---- the new state becomes the current one
     py = qy;

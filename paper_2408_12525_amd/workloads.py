@@ -73,7 +73,8 @@ def make_config(problem, batch, size, obs_w, *, min_size=None, pad_mode=PAD_BORD
                 pos_mode=POS_RANDOM, n_frozen=0, max_steps=1000, max_changes=0, autoreset=1,
                 probs=None, weights=None, target_lo=None, target_hi=None, max_w=None,
                 min_w=None, regions_mode=REGIONS_INCREMENTAL, levels_per_wave=0,
-                obs_store_mode=0, split_step=0, obs_format=0, pinpoint_tile=None, ctrl=None):
+                obs_store_mode=0, split_step=0, obs_format=0, pinpoint_tile=None, ctrl=None,
+                obs_frozen_channel=0):
     """ctrl: {metric index: (lo, hi)} -- targets drawn per episode; pinpoint_tile: tile of each
     pinpoint (-1 keeps the drawn one)."""
     w, lo, hi = default_reward_table(problem)
@@ -101,6 +102,7 @@ def make_config(problem, batch, size, obs_w, *, min_size=None, pad_mode=PAD_BORD
         ctrl_mask=sum(1 << i for i in ctrl),
         ctrl_lo=[ctrl.get(i, (0, 0))[0] for i in range(16)],
         ctrl_hi=[ctrl.get(i, (0, 0))[1] for i in range(16)],
+        obs_frozen_channel=obs_frozen_channel,
     )
 
 
@@ -154,6 +156,7 @@ def random_actions(cfg: dict, seed: int, steps: int, bad_fraction: float = 0.0):
 
 
 def obs_bytes(cfg: dict) -> int:
-    C = NUM_TILES[cfg["problem"]] + (1 if cfg["pad_mode"] == PAD_BORDER else 0)
+    C = (NUM_TILES[cfg["problem"]] + (1 if cfg["pad_mode"] == PAD_BORDER else 0)
+         + (1 if cfg.get("obs_frozen_channel", 0) else 0))
     cells = C * cfg["obs_w"] * cfg["obs_w"]
     return (cells + 7) // 8 if cfg.get("obs_format", 0) else cells

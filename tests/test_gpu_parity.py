@@ -40,6 +40,10 @@ SMALL = [
     ("dungeon64 ow1", wl.make_config(wl.DUNGEON, 4, 40, 1, max_w=64, max_steps=90), 100, {}),
     ("batch of one", wl.make_config(wl.MAZE, 1, 16, 31, max_steps=30), 70, {}),
     ("maze16 bit-packed obs", wl.workload("maze16", batch=77, max_steps=40, obs_format=1), 100, {}),
+    ("maze16 pinpoint channel", wl.workload("maze16_pinpoint", batch=60, max_steps=33, obs_frozen_channel=1, obs_w=31), 100, {}),
+    ("binary32 pinpoint channel ow63 wall pad packed", wl.workload("binary32_rand_ow63", batch=11, max_steps=25, pad_mode=wl.PAD_WALL,
+                                                                   obs_frozen_channel=1, obs_format=1), 60, {}),
+    ("dungeon64 pinpoint channel, nothing frozen", wl.make_config(wl.DUNGEON, 5, 64, 15, max_steps=30, obs_frozen_channel=1), 50, {}),
     ("binary32 rand ow63 bit-packed", wl.workload("binary32_rand_ow63", batch=13, max_steps=30, obs_format=1), 70, {}),
     ("dungeon64 ow5 bit-packed", wl.make_config(wl.DUNGEON, 7, 64, 5, min_size=20, max_steps=30, obs_format=1), 70, {}),
     ("binary16 ow1 bit-packed", wl.make_config(wl.BINARY, 40, 16, 1, max_steps=30, obs_format=1, pad_mode=wl.PAD_WALL), 50, {}),
@@ -63,6 +67,30 @@ def test_small_configs_every_step(label, cfg, steps, extra, lpw, split):
         pytest.skip("a 64-row level fills the wavefront")
     run_parity(dict(cfg, levels_per_wave=lpw, split_step=split), steps,
                label=f"{label} lpw={lpw} split={split}", **extra)
+
+
+def test_pinpoint_channel_after_set_state():
+    dev = torch.device("cuda", 0)
+    cfg = wl.make_config(wl.MAZE, 4, 16, 15, autoreset=0, obs_frozen_channel=1)
+    gpu, cpu = binding.Pcgrl(cfg, 0), oracle.Oracle(cfg)
+    gpu.pcgrl_reset(2)
+    cpu.reset(2)
+    rng = np.random.default_rng(0)
+    tiles = rng.integers(0, 4, size=(4, 16, 16)).astype(np.int8)
+    fro = (rng.random((4, 16, 16)) < 0.2).astype(np.uint8)
+    hw = np.full((4, 2), 16, np.int16)
+    pos = rng.integers(0, 16, size=(4, 2)).astype(np.int16)
+    gpu.pcgrl_set_state(*(torch.from_numpy(a).to(dev) for a in (tiles, fro, hw, pos)))
+    cpu.set_state(tiles, fro, hw, pos)
+    assert_same("obs", gpu.pcgrl_observe(), cpu.observe(), "after set_state")
+    obs = gpu.new_obs()
+    acts = wl.random_actions(cfg, 3, 40)
+    for t in range(40):
+        gpu.pcgrl_step(torch.from_numpy(acts[t]).to(dev), obs)
+        o, _, _ = cpu.step(acts[t])
+        assert_same("obs", obs, o, f"step {t}")
+    compare_state(gpu, cpu, "end")
+    gpu.close()
 
 
 def test_control_targets_and_fractional_weights():
@@ -229,6 +257,7 @@ ROLLOUTS = [
     ("dungeon16 control targets", wl.workload("dungeon16_ctrl", batch=40, max_steps=13), 60, 2),
     ("maze16 pinpointed", wl.workload("maze16_pinpoint", batch=40, max_steps=19), 60, 60),
     ("maze16 bit-packed", wl.workload("maze16", batch=40, max_steps=19, obs_format=1), 40, 5),
+    ("dungeon16 pinpoint channel", wl.workload("dungeon16_ctrl", batch=30, max_steps=17, obs_frozen_channel=1), 40, 40),
 ]
 
 

@@ -294,3 +294,21 @@ def test_control_targets_are_redrawn_per_episode_inside_their_range():
     e.set_state(buf, None, np.array([[1, 8]], np.int16), np.array([[0, 4]], np.int16))
     _, r, _ = e.step(np.array([3], np.int32), want_obs=False)  # a door at column 4: path 4, loss 1
     assert r[0] == 2.0
+
+
+def test_pinpoint_channel_shows_exactly_the_frozen_cells_in_view():
+    # independent formulation: zero-pad the frozen mask, slice the window
+    cfg = wl.make_config(wl.MAZE, 6, 12, 9, min_size=5, n_frozen=5, max_steps=30, obs_frozen_channel=1)
+    env, obs, acts = run(cfg, 40)
+    assert obs.shape[1] == 4 + 1 + 1
+    for t in range(len(acts) + 1):
+        st = env.get_state()
+        for b in range(env.B):
+            h, w = st["hw"][b]
+            py, px = st["pos"][b]
+            fro = np.pad(st["frozen"][b, :h, :w], 9)
+            want = fro[py + 9 - 4: py + 9 - 4 + 9, px + 9 - 4: px + 9 - 4 + 9]
+            assert (obs[b, 5] == want).all()
+            assert (obs[b, :5] == numpy_window(st["tiles"][b], h, w, py, px, 9, 4, True)).all()
+        if t < len(acts):
+            obs, _, _ = env.step(acts[t])
