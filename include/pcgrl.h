@@ -176,6 +176,13 @@ int pcgrl_rollout(pcgrl_ctx* ctx, const int32_t* actions, int32_t n_steps, uint8
 /* Copies the cached metric vectors.  out: device, int32 [batch][M]. */
 int pcgrl_metrics(pcgrl_ctx* ctx, int32_t* out, void* stream);
 
+/* Exact diameter of every level: the largest shortest-path distance between any two connected
+ * walkable cells (Task / Binary domain: "the longest shortest path between any two points"), by a
+ * breadth-first sweep from every walkable cell.  A diagnostic for the error of the two-sweep
+ * estimate, not part of a step: the cost grows with (walkable cells) x (eccentricity), about a
+ * million vector instructions for one open 64x64 level.  out: device, int32 [batch]. */
+int pcgrl_exact_diameter(pcgrl_ctx* ctx, int32_t* out, void* stream);
+
 /* Writes the current observation of every environment without stepping.  obs: device. */
 int pcgrl_observe(pcgrl_ctx* ctx, uint8_t* obs, void* stream);
 

@@ -69,6 +69,8 @@ def lib():
         L.orc_step_range.argtypes = [p, C.c_int, C.c_int, p, p, p, p]
         L.orc_metrics.argtypes = [p, p]
         L.orc_observe.argtypes = [p, p]
+        L.orc_exact_diameters.argtypes = [p, p]
+        L.orc_exact_diameter.argtypes = [p, C.c_int, C.c_int, C.c_int]
         L.orc_get_state.argtypes = [p, p, p, p, p, p]
         L.orc_set_state.argtypes = [p, p, p, p, p]
         L.orc_set_targets.argtypes = [p, p]
@@ -160,6 +162,11 @@ class Oracle:
         self.L.orc_metrics(self.h, _ptr(out))
         return out
 
+    def exact_diameters(self):
+        out = np.zeros(self.B, np.int32)
+        self.L.orc_exact_diameters(self.h, _ptr(out))
+        return out
+
     def observe(self):
         obs = self.new_obs()
         self.L.orc_observe(self.h, _ptr(obs))
@@ -217,6 +224,11 @@ def bfs(tiles, src_tile=-1, src_index=0):
 def diameter_two_pass(tiles) -> int:
     t, h, w = _lvl(tiles)
     return lib().orc_diameter_two_pass(_ptr(t), h, w, w)
+
+
+def exact_diameter(tiles) -> int:
+    t, h, w = _lvl(tiles)
+    return lib().orc_exact_diameter(_ptr(t), h, w, w)
 
 
 def path_nearest(tiles, src_tile, dst_tile) -> int:

@@ -202,6 +202,20 @@ int orc_diameter_two_pass(const int8_t* tiles, int h, int w, int pitch) {
   return far;
 }
 
+/* Binary domain: "the longest shortest path between any two points in the maze", computed
+ * exactly: one breadth-first search from every walkable cell, the largest distance found. */
+int orc_exact_diameter(const int8_t* tiles, int h, int w, int pitch) {
+  static __thread int32_t dist[MAXC];
+  int best = 0;
+  for (int s = 0; s < h * w; ++s) {
+    if (!passable(tiles[(s / w) * pitch + (s % w)])) continue;
+    orc_bfs(tiles, h, w, pitch, -1, s, dist);
+    for (int i = 0; i < h * w; ++i)
+      if (dist[i] > best) best = dist[i];
+  }
+  return best;
+}
+
 /* Shortest distance from any cell of tile src_tile to any cell of tile dst_tile.
  * Reading: with several sources or destinations the nearest pair counts (this is the paper's
  * single player / single door quantity when there is one of each); no source, no destination
@@ -491,6 +505,11 @@ void orc_step(orc_ctx* ctx, const int32_t* actions, uint8_t* obs, float* reward,
 void orc_metrics(const orc_ctx* ctx, int32_t* out) {
   for (int b = 0; b < ctx->cfg.batch; ++b)
     for (int i = 0; i < ctx->M; ++i) out[(size_t)b * ctx->M + i] = ctx->env[b].m[i];
+}
+
+void orc_exact_diameters(const orc_ctx* ctx, int32_t* out) {
+  for (int b = 0; b < ctx->cfg.batch; ++b)
+    out[b] = orc_exact_diameter(ctx->env[b].tiles, ctx->env[b].h, ctx->env[b].w, ctx->cfg.max_w);
 }
 
 void orc_observe(const orc_ctx* ctx, uint8_t* obs) {

@@ -85,6 +85,7 @@ void orc_step_range(orc_ctx* ctx, int env_lo, int env_hi, const int32_t* actions
 void orc_step(orc_ctx* ctx, const int32_t* actions, uint8_t* obs, float* reward, uint8_t* done);
 void orc_metrics(const orc_ctx* ctx, int32_t* out /* [batch][M] */);
 void orc_observe(const orc_ctx* ctx, uint8_t* obs);
+void orc_exact_diameters(const orc_ctx* ctx, int32_t* out /* [batch] */);
 
 /* tiles int8 [batch][max_h][max_w] (-1 outside the active map), frozen uint8 same shape,
  * hw int16 [batch][2], pos int16 [batch][2], counters int32 [batch][3] = t, n_changes, episode */
@@ -108,6 +109,8 @@ int orc_regions(const int8_t* tiles, int h, int w, int pitch);
 void orc_bfs(const int8_t* tiles, int h, int w, int pitch, int src_tile, int src_index,
              int32_t* dist);
 int orc_diameter_two_pass(const int8_t* tiles, int h, int w, int pitch);
+/* exact diameter: the largest shortest-path distance between any two connected walkable cells */
+int orc_exact_diameter(const int8_t* tiles, int h, int w, int pitch);
 int orc_path_nearest(const int8_t* tiles, int h, int w, int pitch, int src_tile, int dst_tile);
 int orc_path_dungeon(const int8_t* tiles, int h, int w, int pitch);
 /* full metric vector of one level for a problem */

@@ -41,7 +41,7 @@ class PcgrlConfig(C.Structure):
 
 EXPORTS = [
     "pcgrl_config_default", "pcgrl_create", "pcgrl_destroy", "pcgrl_reset", "pcgrl_step", "pcgrl_rollout",
-    "pcgrl_metrics", "pcgrl_observe", "pcgrl_get_state", "pcgrl_set_state", "pcgrl_set_targets",
+    "pcgrl_metrics", "pcgrl_exact_diameter", "pcgrl_observe", "pcgrl_get_state", "pcgrl_set_state", "pcgrl_set_targets",
     "pcgrl_get_targets",
     "pcgrl_obs_shape", "pcgrl_obs_bytes", "pcgrl_num_metrics", "pcgrl_num_tiles", "pcgrl_bad_action_count",
     "pcgrl_selftest", "pcgrl_strerror",
@@ -77,6 +77,7 @@ def load():
     L.pcgrl_rollout.argtypes = [p, p, i32, p, i32, p, p, p]
     L.pcgrl_metrics.argtypes = [p, p, p]
     L.pcgrl_observe.argtypes = [p, p, p]
+    L.pcgrl_exact_diameter.argtypes = [p, p, p]
     L.pcgrl_get_state.argtypes = [p, p, p, p, p, p, p]
     L.pcgrl_set_state.argtypes = [p, p, p, p, p, p]
     L.pcgrl_set_targets.argtypes = [p, p, p]
@@ -208,6 +209,13 @@ class Pcgrl:
             out = torch.empty((self.B, self.M), dtype=torch.int32, device=self.device)
         o = self._dev(out, torch.int32, (self.B, self.M), "out")
         _check(self.L.pcgrl_metrics(self.h, o, self._st()), "pcgrl_metrics")
+        return out
+
+    def pcgrl_exact_diameter(self, out=None):
+        if out is None:
+            out = torch.empty((self.B,), dtype=torch.int32, device=self.device)
+        o = self._dev(out, torch.int32, (self.B,), "out")
+        _check(self.L.pcgrl_exact_diameter(self.h, o, self._st()), "pcgrl_exact_diameter")
         return out
 
     def pcgrl_observe(self, obs=None):

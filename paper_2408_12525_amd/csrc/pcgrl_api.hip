@@ -108,6 +108,13 @@ template <int S, int PROBLEM> struct LaunchInit {
   }
 };
 
+template <int S, int PROBLEM> struct LaunchExact {
+  static int run(const pcgrl_ctx* ctx, const KArgs& a, int32_t* out, hipStream_t st) {
+    hipLaunchKernelGGL((exact_diameter_kernel<S, PROBLEM>), dim3(ctx->nwaves), dim3(64), ctx->lds_bytes, st, a, out);
+    return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
+  }
+};
+
 int launch_init(pcgrl_ctx* ctx, int flags, uint64_t seed, uint8_t* obs, hipStream_t st) {
   KArgs a = ctx->base;
   a.flags = flags;
@@ -366,6 +373,12 @@ int pcgrl_metrics(pcgrl_ctx* ctx, int32_t* out, void* stream) {
                      static_cast<hipStream_t>(stream), static_cast<const int32_t*>(ctx->d_metrics),
                      out, ctx->cfg.batch, ctx->M);
   return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
+}
+
+int pcgrl_exact_diameter(pcgrl_ctx* ctx, int32_t* out, void* stream) {
+  if (!ctx || !out) return PCGRL_E_NULL;
+  DeviceGuard guard(ctx->device);
+  return dispatch<LaunchExact>(ctx->S, ctx->cfg.problem, ctx, ctx->base, out, static_cast<hipStream_t>(stream));
 }
 
 int pcgrl_observe(pcgrl_ctx* ctx, uint8_t* obs, void* stream) {

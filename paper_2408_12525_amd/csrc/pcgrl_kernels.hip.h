@@ -780,6 +780,37 @@ __global__ __launch_bounds__(64) void init_kernel(KArgs a) {
   if ((a.flags & kInitObs) && a.obs != nullptr) observe<S, PROBLEM>(a, L, wm, a.obs, p, fz, inside, py, px);
 }
 
+// Exact diameter: a sweep from every walkable cell, the largest eccentricity found.  Cells are
+// taken in row-major order, each group at its own pace; the loop ends when no group has a cell
+// left (every sweep ends because its visited set can only grow).
+template <int S, int PROBLEM>
+__global__ __launch_bounds__(64) void exact_diameter_kernel(KArgs a, int32_t* out) {
+  using W = typename RowWord<S>::T;
+  using PR = Prob<PROBLEM>;
+  extern __shared__ uint32_t lds_all[];
+  Lanes<S> L;
+  WaveMap<S> wm;
+  wm.init(a, L, lds_all);
+  const W* planes = reinterpret_cast<const W*>(a.planes);
+  const size_t ridx = (size_t)wm.envl * S + L.y;
+  W p[PR::P];
+#pragma unroll
+  for (int i = 0; i < PR::P; ++i) p[i] = planes[(size_t)i * a.plane_stride + ridx];
+  const EnvRec er = a.env[wm.envl];
+  const W inside = wm.valid ? inside_row<W>(L.y, er.h, er.w) : (W)0;
+  const W pass = inside & ~channel_row<PROBLEM, W>(p, inside, 1);
+  W todo = pass;
+  int best = 0;
+  for (;;) {
+    const W src = first_cell<S>(L, todo);
+    if (!wave_any<S>(src != 0)) break;
+    todo &= ~src;
+    W unused;
+    best = max(best, sweep<S>(L, src, pass, unused));
+  }
+  if (wm.primary && L.y == 0) out[wm.env] = best;
+}
+
 // One environment step of every level (pcgrl_step), or, with ROLL, `rollout_steps` consecutive
 // steps (pcgrl_rollout) during which the levels never leave the registers: per step only the
 // action is read and the observation, reward and done flag are written.

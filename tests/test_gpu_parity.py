@@ -69,6 +69,30 @@ def test_small_configs_every_step(label, cfg, steps, extra, lpw, split):
                label=f"{label} lpw={lpw} split={split}", **extra)
 
 
+@pytest.mark.parametrize("name,batch", [("binary16", 300), ("maze16", 130), ("binary32_rand_ow3", 90),
+                                        ("dungeon32", 40), ("maze64", 6)])
+def test_exact_diameter_query(name, batch):
+    """All-sources BFS on the GPU against the oracle's, on fresh and on edited levels; the cached
+    two-sweep estimate of the binary problem must never exceed it."""
+    dev = torch.device("cuda", 0)
+    cfg = wl.workload(name, batch=batch, max_steps=10**6, autoreset=0)
+    gpu, cpu = binding.Pcgrl(cfg, 0), oracle.Oracle(cfg)
+    gpu.pcgrl_reset(31)
+    cpu.reset(31, want_obs=False)
+    acts = wl.random_actions(cfg, 32, 60)
+    for rnd in range(3):
+        exact = gpu.pcgrl_exact_diameter().cpu().numpy()
+        assert np.array_equal(exact, cpu.exact_diameters()), f"round {rnd}"
+        if cfg["problem"] == wl.BINARY:
+            est = gpu.pcgrl_metrics().cpu().numpy()[:, 1]
+            assert (est <= exact).all()
+        for t in range(20):
+            a = acts[rnd * 20 + t]
+            gpu.pcgrl_step(torch.from_numpy(a).to(dev))
+            cpu.step(a, want_obs=False)
+    gpu.close()
+
+
 def test_pinpoint_channel_after_set_state():
     dev = torch.device("cuda", 0)
     cfg = wl.make_config(wl.MAZE, 4, 16, 15, autoreset=0, obs_frozen_channel=1)
@@ -125,6 +149,10 @@ def test_set_state_with_hand_built_levels():
         cpu.set_state(buf, fro, hw, pos)
         m = gpu.pcgrl_metrics().cpu().numpy()
         got = dict(zip(wl.metric_names(pid), (int(v) for v in m[0])))
+        exact = gpu.pcgrl_exact_diameter().cpu().numpy()
+        assert np.array_equal(exact, cpu.exact_diameters()), name
+        if "exact_diameter" in expect:
+            assert exact[0] == expect.pop("exact_diameter"), name
         for k, v in expect.items():
             assert got[k] == v, (name, k, got)
         assert_same("metrics", m, cpu.metrics(), name)

@@ -42,6 +42,8 @@ def test_hand_built_level(name):
     pid = levels.PROBLEM_ID[problem]
     m = oracle.level_metrics(pid, tiles)
     got = dict(zip(wl.metric_names(pid), (int(v) for v in m)))
+    if "exact_diameter" in expect:
+        assert oracle.exact_diameter(tiles) == expect.pop("exact_diameter"), name
     for k, v in expect.items():
         assert got[k] == v, (name, k, got)
     # the same level embedded in a larger buffer (row pitch != width) must read the same
@@ -134,6 +136,21 @@ def test_single_instance_dungeon_is_sum_of_two_distances():
         want = 0 if d[p, k] >= brute.INF or d[k, dd] >= brute.INF else d[p, k] + d[k, dd]
         assert oracle.path_dungeon(t) == want
         done += 1
+
+
+def test_exact_diameter_vs_all_pairs():
+    rng = np.random.default_rng(21)
+    for _ in range(120):
+        h, w = rng.integers(1, 8, size=2)
+        t = _random_level(rng, 4, h, w, rng.choice([0.1, 0.3, 0.5]))
+        d = brute.all_pairs(t)
+        fin = d[d < brute.INF]
+        want = int(fin.max()) if fin.size else 0
+        got = oracle.exact_diameter(t)
+        assert got == want
+        if (t != 1).any():
+            m = oracle.level_metrics(wl.BINARY, (t == 1).astype(np.int8))
+            assert m[1] <= got                    # the two-sweep value never exceeds the diameter
 
 
 def test_loss_is_distance_to_range():
