@@ -284,7 +284,7 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   a.obs_frozen_channel = cfg->obs_frozen_channel ? 1 : 0;
   a.envs_per_wave_log2 = ctx->epw == 4 ? 2 : ctx->epw == 2 ? 1 : 0;
   a.use_frozen = cfg->n_frozen > 0 ? 1 : 0;
-  // How the observation is stored (measured on MI355X, see the design notes): streaming stores
+  // How the observation is stored (measured on MI355X): streaming stores
   // keep a small batch's level state in the 4 MB per-XCD L2 from one step to the next instead of
   // evicting it with observation bytes nobody on that XCD reads again; from there up to a few
   // hundred MB ordinary stores win because the 256 MB last-level cache absorbs them; far beyond
