@@ -156,7 +156,9 @@ int pcgrl_reset(pcgrl_ctx* ctx, uint64_t seed, uint8_t* obs, void* stream);
  *   reward : device, float32 [batch]: sum over metrics, in index order, of
  *            weight * (loss before - loss after); exactly 0 when the edit was a no-op.
  *   done   : device, uint8 [batch].
- * reward and done may be NULL. */
+ * reward and done may be NULL.
+ * The call only enqueues one kernel launch, so it may be captured into a HIP graph; a captured
+ * launch keeps the arguments and the reset seed that were current when it was captured. */
 int pcgrl_step(pcgrl_ctx* ctx, const int32_t* actions, uint8_t* obs, float* reward, uint8_t* done,
                void* stream);
 

@@ -59,14 +59,18 @@ def library_path() -> str:
 
 
 def load():
-    """Loads the in-tree library (never builds it); raises if it is not there."""
+    """Loads the in-tree library.  If it has never been built it is compiled first (hipcc); if
+    that is impossible the call raises -- there is no other implementation to fall back to."""
     global _lib
     if _lib is not None:
         return _lib
     path = library_path()
     if not os.path.exists(path):
-        raise PcgrlError(f"{path} is missing: build it first (python -m paper_2408_12525_amd.build); "
-                         "there is no fallback implementation")
+        try:
+            _build.build(force=True)
+        except Exception as e:  # no hipcc, compile error, read-only tree ...
+            raise PcgrlError(f"{path} is missing and could not be built ({e}); "
+                             "there is no fallback implementation") from e
     L = C.CDLL(path)
     p, i32, u64 = C.c_void_p, C.c_int32, C.c_uint64
     L.pcgrl_config_default.argtypes = [i32, C.POINTER(PcgrlConfig)]
