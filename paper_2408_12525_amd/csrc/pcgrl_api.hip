@@ -283,7 +283,7 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   a.obs_packed = cfg->obs_format == PCGRL_OBS_PACKED ? 1 : 0;
   a.obs_frozen_channel = cfg->obs_frozen_channel ? 1 : 0;
   a.envs_per_wave_log2 = ctx->epw == 4 ? 2 : ctx->epw == 2 ? 1 : 0;
-  a.use_frozen = cfg->n_frozen > 0 ? 1 : 0;
+  a.use_frozen = cfg->n_frozen > 0 ? (cfg->obs_frozen_channel ? 3 : 1) : 0;
   // How the observation is stored (measured on MI355X): streaming stores
   // keep a small batch's level state in the 4 MB per-XCD L2 from one step to the next instead of
   // evicting it with observation bytes nobody on that XCD reads again; from there up to a few
@@ -415,7 +415,7 @@ int pcgrl_set_state(pcgrl_ctx* ctx, const int8_t* tiles, const uint8_t* frozen, 
     hipLaunchKernelGGL(set_state_kernel<uint32_t>, dim3((n + 255) / 256), dim3(256), 0, st, ctx->base,
                        ctx->S, ctx->P, ctx->K, tiles, frozen, hw, pos);
   if (hipGetLastError() != hipSuccess) return PCGRL_E_HIP;
-  if (frozen) ctx->base.use_frozen = 1;  // from now on steps have to look pinpoints up
+  if (frozen) ctx->base.use_frozen = ctx->cfg.obs_frozen_channel ? 3 : 1;  // from now on steps have to look pinpoints up
   return launch_init(ctx, kInitMetrics, ctx->base.seed, nullptr, st);
 }
 

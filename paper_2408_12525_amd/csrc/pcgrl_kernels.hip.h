@@ -43,26 +43,27 @@ struct __attribute__((aligned(16))) EnvRec {
 static_assert(sizeof(EnvRec) == 32, "EnvRec must be 32 bytes");
 
 struct KArgs {
+  // the first 64 bytes are everything a step needs to request its loads: one scalar fetch
   void* planes;      // word [P][plane_stride], index env * S + y
   void* frozen;      // word [plane_stride]
   EnvRec* env;       // [B_pad]
   int32_t* metrics;  // [B_pad][16]
   uint32_t* targets; // [B_pad][16], lo | hi << 16 (ranges are clamped to 0..65535)
   const int32_t* actions;
+  int32_t B, plane_stride;
+  int32_t envs_per_wave_log2;  // distinct levels per wavefront = 1 << this; at most 64 / S
+  int32_t use_frozen;     // 0: no level of this context has a pinpoint cell; bit 1: a step needs the pinpoint rows (they are shown in the observation)
   uint8_t* obs;
   float* reward;
   uint8_t* done;
   unsigned long long* bad_actions;
   uint64_t seed;
-  int32_t B, plane_stride;
   int32_t max_h, max_w, min_h, min_w;
   int32_t obs_w, pad_mode, pos_mode, n_frozen, max_steps, max_changes, autoreset, regions_mode;
   int32_t env_obs_bytes;  // bytes of one level's observation: C * obs_w * obs_w, or an eighth (rounded up) when packed
   int32_t obs_packed;     // non-zero: bit-packed observation format
   int32_t obs_frozen_channel;  // non-zero: a last channel marks the pinpoint cells in view
-  int32_t envs_per_wave_log2;  // distinct levels per wavefront = 1 << this; at most 64 / S
   int32_t stream_obs;     // non-zero: write observations with non-temporal stores
-  int32_t use_frozen;     // zero: no level of this context has a pinpoint cell
   int32_t flags;          // init kernel only
   int32_t rollout_steps;  // rollout kernel: steps per launch
   int32_t obs_slots;      // rollout kernel: step t writes observation slot t % obs_slots
@@ -73,6 +74,17 @@ struct KArgs {
   uint32_t ctrl_mask;
   int32_t ctrl_lo[kMaxMetrics], ctrl_hi[kMaxMetrics];
 };
+
+// The calling kernel's argument block (KArgs is the first parameter of every kernel here) read
+// through a pointer the optimiser cannot trace back to the arguments.  Blocks that run once in
+// thousands of steps (a level restarting) read their configuration through it: loads made this way
+// stay inside the block, whereas loads from the by-value argument are hoisted, with all the scalar
+// arithmetic that depends on them, to the top of the kernel where every wavefront pays for them.
+__device__ __forceinline__ const KArgs& cold_args() {
+  auto seg = __builtin_amdgcn_kernarg_segment_ptr();
+  asm volatile("" : "+s"(seg));
+  return *(const KArgs*)seg;
+}
 
 template <int S> struct RowWord { using T = uint32_t; };
 template <> struct RowWord<64> { using T = uint64_t; };
@@ -820,12 +832,15 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 128 : 64) void step_kernel(KAr
   using PR = Prob<PROBLEM>;
   constexpr bool ROLL = MODE == kModeRollout, SPLIT = MODE == kModeSplit;
   extern __shared__ uint32_t lds_all[];
+  // fetch the head of the argument block in one go; the rest arrives while the loads are in flight
+  asm volatile("" ::"s"(a.planes), "s"(a.frozen), "s"(a.env), "s"(a.metrics), "s"(a.targets),
+               "s"(a.actions), "s"(a.B), "s"(a.plane_stride), "s"(a.envs_per_wave_log2), "s"(a.use_frozen));
   Lanes<S> L;
   WaveMap<S> wm;
   wm.init(a, L, lds_all);
   // SPLIT: the workgroup is two wavefronts on the same levels; wavefront 0 does the metrics, the
   // reward and the state stores, wavefront 1 the observation; both load the same (old) state
-  const int role = SPLIT ? (int)(threadIdx.x >> 6) : 0;
+  const int role = SPLIT ? __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) : 0;
   if constexpr (SPLIT) wm.primary = wm.primary && role == 0;
   const bool valid = wm.valid;
   W* planes = reinterpret_cast<W*>(a.planes);
@@ -837,7 +852,7 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 128 : 64) void step_kernel(KAr
 #pragma unroll
   for (int i = 0; i < PR::P; ++i) p[i] = planes[(size_t)i * a.plane_stride + ridx];
   W fz = 0;  // pinpoint rows: resident only in a rollout; a single step keeps a flag with the cell
-  if (ROLL || (a.obs_frozen_channel && a.use_frozen)) fz = frozen[ridx];
+  if (ROLL || (a.use_frozen & 2)) fz = frozen[ridx];
   EnvRec er = a.env[wm.envl];
   int act = a.actions[wm.envl];  // (lanes without a level of their own read a neighbour's and ignore it)
   int mo[PR::M];
@@ -855,8 +870,8 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 128 : 64) void step_kernel(KAr
       tg[4 * q + 3] = t.w;
     }
   }
-#pragma unroll
-  for (int i = 0; i < kTg; ++i) asm volatile("" : "+v"(tg[i]));  // issue these loads here, not at their use
+  // every load above is issued before anything below waits for one of them
+  __builtin_amdgcn_sched_barrier(0);
   int h = er.h, w = er.w, py = er.py, px = er.px;
   W inside = inside_row<W>(L.y, h, w);
   // both wavefronts hold the old state in registers before either of them stores anything
@@ -1003,10 +1018,11 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 128 : 64) void step_kernel(KAr
     }
     // ---- auto-reset: fresh seeded episode for the finished levels; the others keep their registers
     if (any_restart) {
+      const KArgs& ra = cold_args();
       W np[PR::P], nfz;
       int nh, nw, npy, npx;
-      uint64_t nkey = env_key(a.seed, (uint64_t)wm.envl, (uint64_t)(er.episode + 1));
-      begin_episode<S, PROBLEM>(a, L, nkey, np, nfz, nh, nw, npy, npx);
+      uint64_t nkey = env_key(ra.seed, (uint64_t)wm.envl, (uint64_t)(er.episode + 1));
+      begin_episode<S, PROBLEM>(ra, L, nkey, np, nfz, nh, nw, npy, npx);
       W ninside = inside_row<W>(L.y, nh, nw);
       int nm[PR::M];
       full_metrics<S, PROBLEM>(L, np, ninside, restart, nm);
@@ -1026,10 +1042,10 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 128 : 64) void step_kernel(KAr
         planes_dirty = true;
         fz_dirty = true;
         metrics_dirty = true;
-        if (a.ctrl_mask != 0) {
+        if (ra.ctrl_mask != 0) {
 #pragma unroll
           for (int i = 0; i < PR::M; ++i)
-            if ((a.ctrl_mask >> i) & 1u) tg[i] = control_target(a, nkey, i);
+            if ((ra.ctrl_mask >> i) & 1u) tg[i] = control_target(ra, nkey, i);
           targets_dirty = true;
         }
 #pragma unroll
