@@ -533,35 +533,81 @@ struct Slot {
   int slot, copy, copies;
 };
 
-// Writes the observations of the `nvalid` levels of this wavefront.  The window rows are first
-// packed as a bit stream in LDS (bit j of the stream = byte j of the wavefront's contiguous output
-// region, shifted so that 16-bit chunks line up with 16-byte aligned addresses), then every lane
-// widens 16 bits to 16 bytes and issues one aligned 16-byte store.  WIDE = window wider than 32.
-template <int S, int PROBLEM, bool WIDE>
+// Where and how a wavefront writes its observations, as far as that does not depend on the levels
+// themselves.  The window rows are first packed as a bit stream in LDS (bit j of the stream = byte j
+// of the wavefront's contiguous output region, shifted so that 16-bit chunks line up with 16-byte
+// aligned addresses), then every lane widens 16 bits to 16 bytes and issues one aligned 16-byte
+// store.  A single-step kernel works the plan out, and clears the LDS words, while its loads are
+// still in flight.
+struct ObsPlan {
+  uint8_t* base;     // 16-byte aligned address at or just below the wavefront's output region
+  int dbytes, d;     // the region starts dbytes bytes = d stream bits after base
+  int E, total;      // stream bits of one level, and of the wavefront (d included)
+  int lane_off;      // stream position of this lane's level and first channel
+  int q_lo, q_hi;    // aligned 16-byte chunks [q_lo, q_hi) lie wholly inside the region
+  int edge_pos;      // the byte of the partial head (lanes 0-15) or tail (16-31) chunk this lane writes,
+  bool edge_want;    // if any
+  bool active;       // this lane group has a level
+};
+
+__device__ __forceinline__ ObsPlan obs_plan(const KArgs& a, int lane, const Slot& sl, uint8_t* obs,
+                                            int env0, int nvalid) {
+  ObsPlan pl;
+  // One level's part of the stream is E bits long; its output is E bytes (one byte per bit) or,
+  // bit-packed, E / 8 bytes.
+  const bool packed = a.obs_packed != 0;
+  pl.E = packed ? a.env_obs_bytes * 8 : a.env_obs_bytes;
+  uint8_t* region = obs + (size_t)env0 * (size_t)a.env_obs_bytes;
+  pl.dbytes = (int)((uintptr_t)region & 15u);
+  pl.base = region - pl.dbytes;
+  pl.d = packed ? pl.dbytes * 8 : pl.dbytes;
+  pl.total = pl.d + nvalid * pl.E;
+  pl.lane_off = pl.d + sl.slot * pl.E + sl.copy * (a.obs_w * a.obs_w);
+  pl.active = sl.slot < nvalid;
+  // in bytes of output the region is [lo, hi) after base
+  const int lo = pl.dbytes, hi = packed ? pl.total >> 3 : pl.total;
+  pl.q_lo = (lo + 15) >> 4;
+  pl.q_hi = hi >> 4;
+  const int t = lane & 15;
+  const bool is_tail = lane >= 16;
+  const int q = is_tail ? pl.q_hi : 0;
+  pl.edge_pos = (q << 4) + t;
+  pl.edge_want = lane < 32 && (is_tail ? ((hi & 15) != 0 && (pl.q_hi > 0 || lo == 0)) : lo > 0) &&
+                 pl.edge_pos >= lo && pl.edge_pos < hi;
+  return pl;
+}
+// Keeps the plan's values where they were computed (the optimiser would otherwise move them next
+// to their uses, behind the wait for the loads).
+__device__ __forceinline__ void obs_plan_pin(ObsPlan& pl) {
+  int ew = pl.edge_want ? 1 : 0, ac = pl.active ? 1 : 0;
+  asm volatile("" : "+s"(pl.base), "+s"(pl.dbytes), "+s"(pl.d), "+s"(pl.E), "+s"(pl.total), "+s"(pl.q_lo),
+               "+s"(pl.q_hi), "+v"(pl.lane_off), "+v"(pl.edge_pos), "+v"(ew), "+v"(ac));
+  pl.edge_want = ew != 0;
+  pl.active = ac != 0;
+}
+__device__ __forceinline__ void obs_clear(uint32_t* lds, int lane, const ObsPlan& pl) {
+  const int nwords = (pl.total + 31) >> 5;
+  for (int i = lane; i < nwords; i += 64) lds[i] = 0;
+}
+
+// Writes the observations of this wavefront's levels.  WIDE = window wider than 32; CLEARED = the
+// LDS words of the stream are zero already.
+template <int S, int PROBLEM, bool WIDE, bool CLEARED>
 __device__ __forceinline__ void write_obs(const KArgs& a, const Lanes<S>& L, const Slot& sl,
-                                          uint32_t* lds, uint8_t* obs,
+                                          const ObsPlan& pl, uint32_t* lds,
                                           const typename RowWord<S>::T (&p)[Prob<PROBLEM>::P],
                                           typename RowWord<S>::T fz, typename RowWord<S>::T inside,
-                                          int qy, int qx, int env0, int nvalid) {
+                                          int qy, int qx) {
   using W = typename RowWord<S>::T;
   using PR = Prob<PROBLEM>;
   using BW = typename std::conditional<WIDE, uint64_t, uint32_t>::type;  // one window row
   const int ow = a.obs_w, r = ow >> 1;
   const int Cfz = PR::K + (a.pad_mode == kPadBorder ? 1 : 0);  // index of the pinpoint channel, if any
   const int C = Cfz + (a.obs_frozen_channel ? 1 : 0);
-  // One level's part of the stream is E bits long; its output is E bytes (one byte per bit) or,
-  // bit-packed, E / 8 bytes.  dbytes = distance of the region from a 16-byte boundary.
-  const bool packed = a.obs_packed != 0;
-  const int E = packed ? a.env_obs_bytes * 8 : a.env_obs_bytes;
-  uint8_t* region = obs + (size_t)env0 * (size_t)a.env_obs_bytes;
-  const int dbytes = (int)((uintptr_t)region & 15u);
-  const int d = packed ? dbytes * 8 : dbytes;
-  const int total = d + nvalid * E;  // stream length in bits
-  const int nwords = (total + 31) >> 5;
-  for (int i = L.lane; i < nwords; i += 64) lds[i] = 0;
+  if constexpr (!CLEARED) obs_clear(lds, L.lane, pl);
   lds_sync();
 
-  if (sl.slot < nvalid) {
+  if (pl.active) {
     const BW owmask = WIDE ? (BW)((1ull << ow) - 1ull) : (BW)(0xffffffffu >> (32 - ow));
     const int y0 = qy - r, x0 = qx - r;
     const int sr = x0 > 0 ? x0 : 0, sl_ = x0 < 0 ? -x0 : 0;  // one of the two shifts is zero
@@ -582,7 +628,7 @@ __device__ __forceinline__ void write_obs(const KArgs& a, const Lanes<S>& L, con
       const bool real = (y0 + i) == L.y;  // otherwise the row lies above or below the buffer
       const BW in_real = real ? win_in : (BW)0;     // cells of this window row that lie in the map
       const BW pad_bits = real ? out_win : owmask;  // cells of this window row that lie outside
-      int off = d + sl.slot * E + i * ow + sl.copy * cstride;
+      int off = pl.lane_off + i * ow;
       for (int c = sl.copy; c < C; c += sl.copies, off += sl.copies * cstride) {
         BW bits = c < PR::K ? in_real : (BW)0;
 #pragma unroll
@@ -608,21 +654,12 @@ __device__ __forceinline__ void write_obs(const KArgs& a, const Lanes<S>& L, con
   }
   lds_sync();
 
-  uint8_t* base = region - dbytes;  // 16-byte aligned
-  if (packed) {
+  if (a.obs_packed) {
     // bit-packed format: the stream itself is the output, 128 bits per aligned 16-byte chunk
-    const int total_bytes = total >> 3;
-    const int p_lo = (dbytes + 15) >> 4, p_hi = total_bytes >> 4;
     const uint4* lds128 = reinterpret_cast<const uint4*>(lds);
-    for (int q = p_lo + L.lane; q < p_hi; q += 64)
-      *reinterpret_cast<uint4*>(base + ((uint32_t)q << 4)) = lds128[q];
-    const int t = L.lane & 15;
-    const bool is_tail = L.lane >= 16;
-    const int q = is_tail ? p_hi : 0;
-    const bool want = L.lane < 32 && (is_tail ? ((total_bytes & 15) != 0 && (p_hi > 0 || dbytes == 0)) : dbytes > 0);
-    const int pos = (q << 4) + t;
-    if (want && pos >= dbytes && pos < total_bytes)
-      base[pos] = reinterpret_cast<const uint8_t*>(lds)[pos];
+    for (int q = pl.q_lo + L.lane; q < pl.q_hi; q += 64)
+      *reinterpret_cast<uint4*>(pl.base + ((uint32_t)q << 4)) = lds128[q];
+    if (pl.edge_want) pl.base[pl.edge_pos] = reinterpret_cast<const uint8_t*>(lds)[pl.edge_pos];
     return;
   }
   const uint16_t* lds16 = reinterpret_cast<const uint16_t*>(lds);
@@ -635,27 +672,19 @@ __device__ __forceinline__ void write_obs(const KArgs& a, const Lanes<S>& L, con
     return v;
   };
   // chunks that lie completely inside the region: no bounds test, one aligned 16-byte store each
-  const int q_lo = (d + 15) >> 4, q_hi = total >> 4;
   if (a.stream_obs) {
     // the batch's observations exceed the last-level cache: stream them past it
-    for (int q = q_lo + L.lane; q < q_hi; q += 64) {
+    for (int q = pl.q_lo + L.lane; q < pl.q_hi; q += 64) {
       const uint4 v = widen(lds16[q]);
       u32x4 nv = {v.x, v.y, v.z, v.w};
-      __builtin_nontemporal_store(nv, reinterpret_cast<u32x4*>(base + ((uint32_t)q << 4)));
+      __builtin_nontemporal_store(nv, reinterpret_cast<u32x4*>(pl.base + ((uint32_t)q << 4)));
     }
   } else {
-    for (int q = q_lo + L.lane; q < q_hi; q += 64)
-      *reinterpret_cast<uint4*>(base + ((uint32_t)q << 4)) = widen(lds16[q]);
+    for (int q = pl.q_lo + L.lane; q < pl.q_hi; q += 64)
+      *reinterpret_cast<uint4*>(pl.base + ((uint32_t)q << 4)) = widen(lds16[q]);
   }
   // the partial chunk at the head (lanes 0-15, one byte each) and at the tail (lanes 16-31)
-  {
-    const int t = L.lane & 15;
-    const bool is_tail = L.lane >= 16;
-    const int q = is_tail ? q_hi : 0;
-    const bool want = L.lane < 32 && (is_tail ? ((total & 15) != 0 && (q_hi > 0 || d == 0)) : d > 0);
-    const int pos = (q << 4) + t;
-    if (want && pos >= d && pos < total) base[pos] = (uint8_t)((lds16[q] >> t) & 1u);
-  }
+  if (pl.edge_want) pl.base[pl.edge_pos] = (uint8_t)((lds16[pl.edge_pos >> 4] >> (pl.edge_pos & 15)) & 1u);
 }
 
 // ------------------------------------------------------------------ kernels
@@ -714,16 +743,16 @@ template <int S> struct WaveMap {
   }
 };
 
-template <int S, int PROBLEM>
+template <int S, int PROBLEM, bool CLEARED = false>
 __device__ __forceinline__ void observe(const KArgs& a, const Lanes<S>& L, const WaveMap<S>& wm,
-                                        uint8_t* obs,
+                                        const ObsPlan& pl,
                                         const typename RowWord<S>::T (&p)[Prob<PROBLEM>::P],
                                         typename RowWord<S>::T fz, typename RowWord<S>::T inside,
                                         int qy, int qx) {
   if (a.obs_w > 32)
-    write_obs<S, PROBLEM, true>(a, L, wm.sl, wm.lds, obs, p, fz, inside, qy, qx, wm.env0, wm.nvalid);
+    write_obs<S, PROBLEM, true, CLEARED>(a, L, wm.sl, pl, wm.lds, p, fz, inside, qy, qx);
   else
-    write_obs<S, PROBLEM, false>(a, L, wm.sl, wm.lds, obs, p, fz, inside, qy, qx, wm.env0, wm.nvalid);
+    write_obs<S, PROBLEM, false, CLEARED>(a, L, wm.sl, pl, wm.lds, p, fz, inside, qy, qx);
 }
 
 // Reset / refresh / observe: flags choose between generating a fresh episode 0 from the seed or
@@ -789,7 +818,8 @@ __global__ __launch_bounds__(64) void init_kernel(KArgs a) {
     if ((a.ctrl_mask >> L.y) & 1u) t = control_target(a, er.key, L.y);
     a.targets[(size_t)wm.env * kMaxMetrics + L.y] = t;
   }
-  if ((a.flags & kInitObs) && a.obs != nullptr) observe<S, PROBLEM>(a, L, wm, a.obs, p, fz, inside, py, px);
+  if ((a.flags & kInitObs) && a.obs != nullptr)
+    observe<S, PROBLEM>(a, L, wm, obs_plan(a, L.lane, wm.sl, a.obs, wm.env0, wm.nvalid), p, fz, inside, py, px);
 }
 
 // Exact diameter: a sweep from every walkable cell, the largest eccentricity found.  Cells are
@@ -823,6 +853,85 @@ __global__ __launch_bounds__(64) void exact_diameter_kernel(KArgs a, int32_t* ou
   if (wm.primary && L.y == 0) out[wm.env] = best;
 }
 
+// The observation wavefront of the split kernel: loads the level, applies the edit in registers
+// (it stores nothing but the observation), finds the agent's next cell and writes the window
+// around it.  It reads what the metrics wavefront of the same workgroup reads, and the workgroup
+// barrier keeps that wavefront from storing the new state before these loads were issued.
+template <int S, int PROBLEM>
+__device__ __forceinline__ void obs_wave_step(const KArgs& a, const Lanes<S>& L, const WaveMap<S>& wm) {
+  using W = typename RowWord<S>::T;
+  using PR = Prob<PROBLEM>;
+  const W* planes = reinterpret_cast<const W*>(a.planes);
+  const size_t ridx = (size_t)wm.envl * S + L.y;
+  W p[PR::P];
+#pragma unroll
+  for (int i = 0; i < PR::P; ++i) p[i] = planes[(size_t)i * a.plane_stride + ridx];
+  // (the pinpoint rows are loaded whether or not they are shown: no branch between the loads)
+  W fz = reinterpret_cast<const W*>(a.frozen)[ridx];
+  const uint4* erp = reinterpret_cast<const uint4*>(a.env + wm.envl);
+  const uint4 er0 = erp[0], er1 = erp[1];
+  const int act = a.actions[wm.envl];
+  __builtin_amdgcn_sched_barrier(0);
+  if (!(a.use_frozen & 2)) fz = 0;
+  ObsPlan pl = obs_plan(a, L.lane, wm.sl, a.obs, wm.env0, wm.nvalid);
+  obs_plan_pin(pl);
+  obs_clear(wm.lds, L.lane, pl);
+  __builtin_amdgcn_sched_barrier(0);
+  __syncthreads();
+
+  int h = (int)(er0.x & 0xffu), w = (int)((er0.x >> 8) & 0xffu);
+  const int py = (int)((er0.x >> 16) & 0xffu), px = (int)(er0.x >> 24);
+  int t = (int)er0.y + 1;
+  const uint64_t key = (uint64_t)er1.x | ((uint64_t)er1.y << 32);
+  W inside = inside_row<W>(L.y, h, w);
+  // the edit: writing the tile that is already there changes nothing, so the old tile is only
+  // looked at when changes are counted against a budget
+  const bool at_row = L.y == py;
+  const bool may_write = wm.valid && act >= 0 && act < PR::K && er1.z == 0;
+  bool done = t >= a.max_steps;
+  if (a.max_changes > 0) {
+    int old_code = 0;
+#pragma unroll
+    for (int i = 0; i < PR::P; ++i) old_code |= (L.gany(at_row && ((p[i] >> px) & 1)) ? 1 : 0) << i;
+    const int n_changes = (int)er0.z + ((may_write && act != old_code) ? 1 : 0);
+    done = done || n_changes >= a.max_changes;
+  }
+  if (may_write && at_row) {
+#pragma unroll
+    for (int i = 0; i < PR::P; ++i) p[i] = (p[i] & ~((W)1 << px)) | ((W)((act >> i) & 1) << px);
+  }
+  int qy = py, qx = px;
+  if (a.pos_mode == kPosScan) {
+    qx += 1;
+    if (qx >= w) {
+      qx = 0;
+      qy += 1;
+      if (qy >= h) qy = 0;
+    }
+  } else {
+    uint64_t u = draw(key, 3, (uint32_t)t);
+    qy = below((uint32_t)(u >> 32), h);
+    qx = below((uint32_t)u, w);
+  }
+  const bool restart = wm.valid && done && a.autoreset != 0;
+  if (wave_any<S>(restart)) {  // the observation then shows the first state of the next episode
+    const KArgs& ra = cold_args();
+    W np[PR::P], nfz;
+    int nh, nw, npy, npx;
+    uint64_t nkey = env_key(ra.seed, (uint64_t)wm.envl, (uint64_t)((int)er0.w + 1));
+    begin_episode<S, PROBLEM>(ra, L, nkey, np, nfz, nh, nw, npy, npx);
+    if (restart) {
+#pragma unroll
+      for (int i = 0; i < PR::P; ++i) p[i] = np[i];
+      fz = nfz;
+      inside = inside_row<W>(L.y, nh, nw);
+      qy = npy;
+      qx = npx;
+    }
+  }
+  observe<S, PROBLEM, true>(a, L, wm, pl, p, fz, inside, qy, qx);
+}
+
 // One environment step of every level (pcgrl_step), or, with ROLL, `rollout_steps` consecutive
 // steps (pcgrl_rollout) during which the levels never leave the registers: per step only the
 // action is read and the observation, reward and done flag are written.
@@ -839,9 +948,15 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 128 : 64) void step_kernel(KAr
   WaveMap<S> wm;
   wm.init(a, L, lds_all);
   // SPLIT: the workgroup is two wavefronts on the same levels; wavefront 0 does the metrics, the
-  // reward and the state stores, wavefront 1 the observation; both load the same (old) state
-  const int role = SPLIT ? __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) : 0;
-  if constexpr (SPLIT) wm.primary = wm.primary && role == 0;
+  // reward and the state stores (the code below, without its observation parts), wavefront 1 the
+  // observation; both load the same (old) state
+  if constexpr (SPLIT) {
+    if (__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) == 1) {
+      obs_wave_step<S, PROBLEM>(a, L, wm);
+      __builtin_amdgcn_endpgm();  // (not a return: the two paths must not meet again, or the
+                                  // compiler makes this one wait for the other one's loads)
+    }
+  }
   const bool valid = wm.valid;
   W* planes = reinterpret_cast<W*>(a.planes);
   W* frozen = reinterpret_cast<W*>(a.frozen);
@@ -853,7 +968,8 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 128 : 64) void step_kernel(KAr
   for (int i = 0; i < PR::P; ++i) p[i] = planes[(size_t)i * a.plane_stride + ridx];
   W fz = 0;  // pinpoint rows: resident only in a rollout; a single step keeps a flag with the cell
   if (ROLL || (a.use_frozen & 2)) fz = frozen[ridx];
-  EnvRec er = a.env[wm.envl];
+  const uint4* erp = reinterpret_cast<const uint4*>(a.env + wm.envl);
+  const uint4 er0 = erp[0], er1 = erp[1];  // unpacked below, after all loads are under way
   int act = a.actions[wm.envl];  // (lanes without a level of their own read a neighbour's and ignore it)
   int mo[PR::M];
   load_metrics<S, PROBLEM>(a.metrics + (size_t)wm.envl * kMaxMetrics, mo);
@@ -872,7 +988,23 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 128 : 64) void step_kernel(KAr
   }
   // every load above is issued before anything below waits for one of them
   __builtin_amdgcn_sched_barrier(0);
-  int h = er.h, w = er.w, py = er.py, px = er.px;
+  // a single step stages one observation: where it goes is worked out, and its LDS words are
+  // cleared, in the shadow of the loads
+  ObsPlan pl;
+  if constexpr (MODE == kModeStep) {
+    pl = obs_plan(a, L.lane, wm.sl, a.obs, wm.env0, wm.nvalid);
+    obs_plan_pin(pl);
+    if (a.obs != nullptr) obs_clear(wm.lds, L.lane, pl);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  EnvRec er;
+  er.t = (int32_t)er0.y;
+  er.n_changes = (int32_t)er0.z;
+  er.episode = (int32_t)er0.w;
+  er.key = (uint64_t)er1.x | ((uint64_t)er1.y << 32);
+  er.cell_frozen = er1.z;
+  er.pad_ = 0;
+  int h = (int)(er0.x & 0xffu), w = (int)((er0.x >> 8) & 0xffu), py = (int)((er0.x >> 16) & 0xffu), px = (int)(er0.x >> 24);
   W inside = inside_row<W>(L.y, h, w);
   // both wavefronts hold the old state in registers before either of them stores anything
   if constexpr (SPLIT) __syncthreads();
@@ -889,7 +1021,10 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 128 : 64) void step_kernel(KAr
     }
     uint8_t* obs = a.obs;
     if constexpr (ROLL) {
-      if (obs != nullptr) obs += (size_t)(step % a.obs_slots) * (size_t)a.B * (size_t)a.env_obs_bytes;
+      if (obs != nullptr) {
+        obs += (size_t)(step % a.obs_slots) * (size_t)a.B * (size_t)a.env_obs_bytes;
+        pl = obs_plan(a, L.lane, wm.sl, obs, wm.env0, wm.nvalid);
+      }
     }
 
     // ---- edit (Methods / Training: the agent may change the tile it stands on)
@@ -945,11 +1080,8 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 128 : 64) void step_kernel(KAr
     // wavefronts flood first and store later was measured and does not pay.)
     const bool any_restart = wave_any<S>(restart);
     const bool obs_late = any_restart;
-    if (obs != nullptr && !obs_late && (!SPLIT || role == 1))
-      observe<S, PROBLEM>(a, L, wm, obs, p, fz, inside, qy, qx);
-    if constexpr (SPLIT) {
-      // the observation wavefront is done, unless a restart makes it wait for the new level
-      if (role == 1 && !any_restart) return;
+    if constexpr (!SPLIT) {
+      if (obs != nullptr && !obs_late) observe<S, PROBLEM, !ROLL>(a, L, wm, pl, p, fz, inside, qy, qx);
     }
 
     // ---- metrics, only where the edit modified the map (Methods / Task)
@@ -1067,8 +1199,9 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 128 : 64) void step_kernel(KAr
       if (a.reward) a.reward[(size_t)step * a.B + wm.env] = reward;
       if (a.done) a.done[(size_t)step * a.B + wm.env] = done ? 1 : 0;
     }
-    if (obs != nullptr && obs_late && (!SPLIT || role == 1))
-      observe<S, PROBLEM>(a, L, wm, obs, p, fz, inside, qy, qx);
+    if constexpr (!SPLIT) {
+      if (obs != nullptr && obs_late) observe<S, PROBLEM, !ROLL>(a, L, wm, pl, p, fz, inside, qy, qx);
+    }
 
     // ---- the new state becomes the current one
     py = qy;
@@ -1103,6 +1236,7 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 128 : 64) void step_kernel(KAr
       for (int q = 0; q < kTg / 4; ++q) tv[q] = make_uint4(tg[4 * q], tg[4 * q + 1], tg[4 * q + 2], tg[4 * q + 3]);
     }
   }
+  if constexpr (SPLIT) __builtin_amdgcn_endpgm();  // see the observation wavefront's exit above
 }
 
 // ------------------------------------------------- plain-layout conversion
