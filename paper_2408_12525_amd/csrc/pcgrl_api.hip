@@ -232,9 +232,9 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
     return PCGRL_E_CONFIG;
   }
   // Two wavefronts per level group (metrics | observation) shorten the dependent chain of a
-  // launch at the price of loading and editing twice.  Measured: a gain of 2-9 % for 16x16 levels
-  // at 512..2048 wavefronts, a loss everywhere else.
-  ctx->split = (ctx->S == 16 && ctx->nwaves >= 512 && ctx->nwaves <= 2048) ? 1 : 0;
+  // launch at the price of loading the level twice.  Measured: a gain of 10-25 % for 16x16 levels
+  // up to 2048 wavefronts, a few percent either way above that and for the larger size classes.
+  ctx->split = (ctx->S == 16 && ctx->nwaves <= 2048) ? 1 : 0;
   if (cfg->split_step == PCGRL_SPLIT_OFF) ctx->split = 0;
   if (cfg->split_step == PCGRL_SPLIT_ON) ctx->split = 1;
 
