@@ -65,6 +65,7 @@ extern "C" {
 #define PCGRL_OBS_STORE_AUTO 0   /* choose from the size of one step's observations */
 #define PCGRL_OBS_STORE_CACHED 1 /* ordinary stores */
 #define PCGRL_OBS_STORE_STREAM 2 /* non-temporal stores */
+#define PCGRL_OBS_STORE_THROUGH 3 /* stores that write through the L2 as they are issued */
 
 #define PCGRL_SPLIT_AUTO 0 /* decide from the number of wavefronts the batch needs */
 #define PCGRL_SPLIT_OFF 1  /* one wavefront per level group does the whole step */

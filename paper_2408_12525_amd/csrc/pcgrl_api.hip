@@ -20,6 +20,7 @@ struct pcgrl_ctx {
   size_t lds_bytes;  // per wavefront
   int split;         // pcgrl_step with an observation uses the two-wavefront kernel
   size_t obs_bytes;  // bytes of one level's observation in the chosen format
+  int store_step, store_roll;  // how a step / a rollout launch stores observations (kStore*)
   KArgs base;  // device pointers and configuration, copied into every launch
   void* d_planes;
   void* d_frozen;
@@ -59,7 +60,7 @@ int check_config(const pcgrl_config* c) {
   if (c->max_steps < 1 || c->max_changes < 0) return PCGRL_E_CONFIG;
   if (c->regions_mode != PCGRL_REGIONS_INCREMENTAL && c->regions_mode != PCGRL_REGIONS_RECOUNT) return PCGRL_E_CONFIG;
   if (c->levels_per_wave < 0 || c->levels_per_wave > 4) return PCGRL_E_CONFIG;
-  if (c->obs_store_mode < 0 || c->obs_store_mode > 2) return PCGRL_E_CONFIG;
+  if (c->obs_store_mode < 0 || c->obs_store_mode > 3) return PCGRL_E_CONFIG;
   if (c->split_step < 0 || c->split_step > 2) return PCGRL_E_CONFIG;
   if (c->obs_format != PCGRL_OBS_ONEHOT_U8 && c->obs_format != PCGRL_OBS_PACKED) return PCGRL_E_CONFIG;
   for (int j = 0; j < 8; ++j)
@@ -284,16 +285,24 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   a.obs_frozen_channel = cfg->obs_frozen_channel ? 1 : 0;
   a.envs_per_wave_log2 = ctx->epw == 4 ? 2 : ctx->epw == 2 ? 1 : 0;
   a.use_frozen = cfg->n_frozen > 0 ? (cfg->obs_frozen_channel ? 3 : 1) : 0;
-  // How the observation is stored (measured on MI355X): streaming stores
-  // keep a small batch's level state in the 4 MB per-XCD L2 from one step to the next instead of
-  // evicting it with observation bytes nobody on that XCD reads again; from there up to a few
-  // hundred MB ordinary stores win because the 256 MB last-level cache absorbs them; far beyond
-  // it streaming stores reach HBM at a higher rate again.
+  // How the observation is stored (measured on MI355X).  A launch per step ends with the L2
+  // write-back of whatever its stores left dirty, after the last wavefront: stores that write
+  // through as they are issued overlap that traffic with the rest of the step (13 % of the step
+  // at 20 MB of observations per step, a few percent at 200 MB); from about 256 MB per step on,
+  // ordinary stores, which the 256 MB last-level cache absorbs, are ahead, and far beyond the
+  // cache non-temporal stores.  A rollout launch has no such tail per step: non-temporal stores
+  // for small batches (they keep the observation bytes out of the L2 that holds the action
+  // stream), ordinary ones above, non-temporal ones far beyond the cache.
   {
     const size_t obs_step_bytes = (size_t)cfg->batch * E;
-    a.stream_obs = (obs_step_bytes <= ((size_t)32 << 20) || obs_step_bytes > ((size_t)448 << 20)) ? 1 : 0;
-    if (cfg->obs_store_mode == PCGRL_OBS_STORE_CACHED) a.stream_obs = 0;
-    if (cfg->obs_store_mode == PCGRL_OBS_STORE_STREAM) a.stream_obs = 1;
+    const size_t MB = (size_t)1 << 20;
+    ctx->store_step = obs_step_bytes <= 256 * MB ? kStoreThrough : obs_step_bytes <= 448 * MB ? kStoreCached : kStoreStream;
+    ctx->store_roll = (obs_step_bytes <= 32 * MB || obs_step_bytes > 448 * MB) ? kStoreStream : kStoreCached;
+    const int forced = cfg->obs_store_mode == PCGRL_OBS_STORE_CACHED ? kStoreCached
+                       : cfg->obs_store_mode == PCGRL_OBS_STORE_STREAM ? kStoreStream
+                       : cfg->obs_store_mode == PCGRL_OBS_STORE_THROUGH ? kStoreThrough : -1;
+    if (forced >= 0) ctx->store_step = ctx->store_roll = forced;
+    a.stream_obs = ctx->store_step;
   }
   for (int k = 0; k < 8; ++k) a.cdf[k] = cfg->init_cdf[k];
   for (int i = 0; i < kMaxMetrics; ++i) {
@@ -362,6 +371,7 @@ int pcgrl_rollout(pcgrl_ctx* ctx, const int32_t* actions, int32_t n_steps, uint8
   a.done = done;
   a.rollout_steps = n_steps;
   a.obs_slots = obs ? obs_slots : 1;
+  a.stream_obs = ctx->store_roll;
   return dispatch<LaunchRollout>(ctx->S, ctx->cfg.problem, ctx, a, static_cast<hipStream_t>(stream));
 }
 

@@ -25,6 +25,7 @@ enum : int { kBinary = 0, kMaze = 1, kDungeon = 2 };
 enum : int { kPadBorder = 0, kPadWall = 1 };
 enum : int { kPosScan = 0, kPosRandom = 1 };
 enum : int { kRegionsIncremental = 0, kRegionsRecount = 1 };
+enum : int { kStoreCached = 0, kStoreStream = 1, kStoreThrough = 2 };
 enum : int { kInitGenerate = 1, kInitMetrics = 2, kInitObs = 4, kInitTargets = 8 };
 // step kernel variants: one step per launch; the same with the work of a wavefront split over
 // two (a metrics wavefront and an observation wavefront per workgroup); n steps per launch
@@ -63,7 +64,7 @@ struct KArgs {
   int32_t env_obs_bytes;  // bytes of one level's observation: C * obs_w * obs_w, or an eighth (rounded up) when packed
   int32_t obs_packed;     // non-zero: bit-packed observation format
   int32_t obs_frozen_channel;  // non-zero: a last channel marks the pinpoint cells in view
-  int32_t stream_obs;     // non-zero: write observations with non-temporal stores
+  int32_t stream_obs;     // how observations are stored: kStoreCached / kStoreStream / kStoreThrough
   int32_t flags;          // init kernel only
   int32_t rollout_steps;  // rollout kernel: steps per launch
   int32_t obs_slots;      // rollout kernel: step t writes observation slot t % obs_slots
@@ -672,8 +673,18 @@ __device__ __forceinline__ void write_obs(const KArgs& a, const Lanes<S>& L, con
     return v;
   };
   // chunks that lie completely inside the region: no bounds test, one aligned 16-byte store each
-  if (a.stream_obs) {
-    // the batch's observations exceed the last-level cache: stream them past it
+  if (a.stream_obs == kStoreThrough) {
+    // Agent-scope stores: the L2 passes them on at once instead of keeping the lines dirty until
+    // the write-back at the end of the kernel, which would otherwise follow the last wavefront
+    // and cost about as long as the stores themselves.  (The compiler has no builtin for a
+    // 16-byte store with a scope; nothing in the kernel reads these bytes back.)
+    for (int q = pl.q_lo + L.lane; q < pl.q_hi; q += 64) {
+      const uint4 v = widen(lds16[q]);
+      u32x4 nv = {v.x, v.y, v.z, v.w};
+      asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(pl.base + ((uint32_t)q << 4)), "v"(nv));
+    }
+  } else if (a.stream_obs == kStoreStream) {
+    // far more than the last-level cache holds: stream the bytes past it
     for (int q = pl.q_lo + L.lane; q < pl.q_hi; q += 64) {
       const uint4 v = widen(lds16[q]);
       u32x4 nv = {v.x, v.y, v.z, v.w};
@@ -988,6 +999,12 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 128 : 64) void step_kernel(KAr
   }
   // every load above is issued before anything below waits for one of them
   __builtin_amdgcn_sched_barrier(0);
+  // the observation wavefront has issued its loads of the old state before this wavefront goes
+  // on to store the new one (the barrier is passed with the loads still in flight)
+  if constexpr (SPLIT) {
+    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+  }
   // a single step stages one observation: where it goes is worked out, and its LDS words are
   // cleared, in the shadow of the loads
   ObsPlan pl;
@@ -1006,8 +1023,6 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 128 : 64) void step_kernel(KAr
   er.pad_ = 0;
   int h = (int)(er0.x & 0xffu), w = (int)((er0.x >> 8) & 0xffu), py = (int)((er0.x >> 16) & 0xffu), px = (int)(er0.x >> 24);
   W inside = inside_row<W>(L.y, h, w);
-  // both wavefronts hold the old state in registers before either of them stores anything
-  if constexpr (SPLIT) __syncthreads();
   bool planes_dirty = false, fz_dirty = false;  // ROLL: what has to be written back at the end
   bool metrics_dirty = false, targets_dirty = false;
   W next_fz_row = 0;

@@ -69,6 +69,29 @@ def test_small_configs_every_step(label, cfg, steps, extra, lpw, split):
                label=f"{label} lpw={lpw} split={split}", **extra)
 
 
+@pytest.mark.parametrize("mode", [1, 2, 3], ids=["cached", "non-temporal", "write-through"])
+@pytest.mark.parametrize("name,batch,split", [("maze16", 70, 2), ("binary32_rand_ow63", 9, 1), ("maze64", 5, 1)])
+def test_every_way_of_storing_the_observation(name, batch, split, mode):
+    """The three store instructions the library chooses between by the size of a step's output,
+    each forced on a small batch: steps (split and unsplit kernel) and a rollout."""
+    cfg = wl.workload(name, batch=batch, max_steps=30, obs_store_mode=mode, split_step=split)
+    run_parity(cfg, 45, label=f"{name} store mode {mode}")
+    dev = torch.device("cuda", 0)
+    T = 37
+    acts_np = wl.random_actions(cfg, 5, T)
+    gpu, cpu = binding.Pcgrl(cfg, 0), oracle.Oracle(cfg)
+    gpu.pcgrl_reset(3)
+    cpu.reset(3)
+    obs = torch.zeros((2,) + gpu.obs_shape, dtype=torch.uint8, device=dev)
+    gpu.pcgrl_rollout(torch.from_numpy(acts_np).to(dev), obs)
+    want = {}
+    for t in range(T):
+        want[t % 2] = cpu.step(acts_np[t])[0]
+    for k, o in want.items():
+        assert_same("obs", obs[k], o, f"rollout slot {k}, store mode {mode}")
+    gpu.close()
+
+
 @pytest.mark.parametrize("name,batch", [("binary16", 300), ("maze16", 130), ("binary32_rand_ow3", 90),
                                         ("dungeon32", 40), ("maze64", 6)])
 def test_exact_diameter_query(name, batch):
@@ -211,7 +234,7 @@ def test_argument_errors_are_reported_not_raised_by_the_gpu():
     bad = wl.workload("maze16", batch=4)
     for field, val in (("obs_w", 64), ("max_h", 65), ("batch", 0), ("problem", 3), ("n_frozen", 9),
                        ("min_h", 17), ("max_steps", 0), ("pad_mode", 2), ("levels_per_wave", 5),
-                       ("split_step", 3), ("obs_store_mode", 3)):
+                       ("split_step", 3), ("obs_store_mode", 4)):
         with pytest.raises(binding.PcgrlError):
             binding.Pcgrl(dict(bad, **{field: val}), 0)
     env = binding.Pcgrl(bad, 0)
