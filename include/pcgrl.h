@@ -123,6 +123,11 @@ typedef struct {
   int32_t ctrl_hi[PCGRL_MAX_METRICS];
   int32_t obs_frozen_channel; /* non-zero: the observation gets one more (last) channel that is 1 on
                            the pinpoint cells in view, so that the agent can see what it cannot edit */
+  int32_t split_obs_levels; /* tuning only: when a step runs as metrics wavefront + observation
+                           wavefronts (PCGRL_SPLIT_*), how many levels one observation wavefront
+                           writes: 0 = automatic; 1, 2 or 4, at most what the metrics wavefront
+                           holds (levels_per_wave); each workgroup then has that many more
+                           observation wavefronts */
 } pcgrl_config;
 
 /* Fills *cfg with this library's defaults for a problem: fixed 16x16 map, window 31, border

@@ -36,6 +36,7 @@ class PcgrlConfig(C.Structure):
         ("ctrl_lo", C.c_int32 * MAX_METRICS),
         ("ctrl_hi", C.c_int32 * MAX_METRICS),
         ("obs_frozen_channel", C.c_int32),
+        ("split_obs_levels", C.c_int32),
     ]
 
 

@@ -18,7 +18,9 @@ struct pcgrl_ctx {
   int epw;  // distinct levels per wavefront (a divisor of G)
   size_t word_bytes;
   size_t lds_bytes;  // per wavefront
-  int split;         // pcgrl_step with an observation uses the two-wavefront kernel
+  int split;         // pcgrl_step with an observation uses the metrics | observation kernel, with
+  int split_m, split_o, split_groups;  // this many levels per metrics / observation wavefront and workgroups
+  size_t split_lds_wave;  // LDS bytes of one observation wavefront there
   size_t obs_bytes;  // bytes of one level's observation in the chosen format
   int store_step, store_roll;  // how a step / a rollout launch stores observations (kStore*)
   KArgs base;  // device pointers and configuration, copied into every launch
@@ -62,6 +64,7 @@ int check_config(const pcgrl_config* c) {
   if (c->levels_per_wave < 0 || c->levels_per_wave > 4) return PCGRL_E_CONFIG;
   if (c->obs_store_mode < 0 || c->obs_store_mode > 3) return PCGRL_E_CONFIG;
   if (c->split_step < 0 || c->split_step > 2) return PCGRL_E_CONFIG;
+  if (c->split_obs_levels < 0 || c->split_obs_levels > 4) return PCGRL_E_CONFIG;
   if (c->obs_format != PCGRL_OBS_ONEHOT_U8 && c->obs_format != PCGRL_OBS_PACKED) return PCGRL_E_CONFIG;
   for (int j = 0; j < 8; ++j)
     if (c->pinpoint_tile[j] < -1 || c->pinpoint_tile[j] >= tiles_of(c->problem)) return PCGRL_E_CONFIG;
@@ -90,9 +93,11 @@ template <int S, int PROBLEM> struct LaunchStep {
     return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
   }
 };
-template <int S, int PROBLEM> struct LaunchSplit {  // one workgroup of two wavefronts per level group
+template <int S, int PROBLEM> struct LaunchSplit {  // a metrics wavefront and its observation wavefronts per workgroup
   static int run(const pcgrl_ctx* ctx, const KArgs& a, hipStream_t st) {
-    hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeSplit>), dim3(ctx->nwaves), dim3(128), ctx->lds_bytes, st, a);
+    const int obs_waves = ctx->split_m / ctx->split_o;
+    hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeSplit>), dim3(ctx->split_groups), dim3(64 * (1 + obs_waves)),
+                       obs_waves * ctx->split_lds_wave, st, a);
     return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
   }
 };
@@ -222,22 +227,36 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
     while (ctx->epw * 2 <= cfg->levels_per_wave && ctx->epw * 2 <= ctx->G) ctx->epw *= 2;
   }
   ctx->nwaves = (cfg->batch + ctx->epw - 1) / ctx->epw;
-  ctx->B_pad = ctx->nwaves * ctx->epw;
+  ctx->B_pad = (cfg->batch + ctx->G - 1) / ctx->G * ctx->G;
   ctx->word_bytes = ctx->S == 64 ? 8 : 4;
   const size_t E1 = (size_t)ctx->C * cfg->obs_w * cfg->obs_w;  // one-hot cells of one observation
   const size_t E = cfg->obs_format == PCGRL_OBS_PACKED ? (E1 + 7) / 8 : E1;  // its bytes
   ctx->obs_bytes = E;
-  ctx->lds_bytes = ((8 * 15 + (size_t)ctx->epw * (E1 + 8) + 31) / 32 + 6) * 4;
+  auto lds_for = [&](int levels) { return ((8 * 15 + (size_t)levels * (E1 + 8) + 31) / 32 + 6) * 4; };
+  ctx->lds_bytes = lds_for(ctx->epw);
   if (ctx->lds_bytes > 64 * 1024) {
     delete ctx;
     return PCGRL_E_CONFIG;
   }
   // Two wavefronts per level group (metrics | observation) shorten the dependent chain of a
   // launch at the price of loading the level twice.  Measured: a gain of 10-25 % for 16x16 levels
-  // up to 2048 wavefronts, a few percent either way above that and for the larger size classes.
-  ctx->split = (ctx->S == 16 && ctx->nwaves <= 2048) ? 1 : 0;
+  // up to 2048 wavefronts and of 7 % for 32x32 levels with a 12 KB observation, a few percent
+  // either way elsewhere.
+  ctx->split = ((ctx->S == 16 && ctx->nwaves <= 2048) || (ctx->S == 32 && E >= 8192 && ctx->nwaves <= 8192)) ? 1 : 0;
   if (cfg->split_step == PCGRL_SPLIT_OFF) ctx->split = 0;
   if (cfg->split_step == PCGRL_SPLIT_ON) ctx->split = 1;
+  // Shape of the split step: one metrics wavefront carries as many levels as the explicit choice
+  // (or the automatic one above) says, and the observation can be shared out over several
+  // wavefronts of split_o levels each (measured: within 3 % of one observation wavefront, which
+  // stays the default).
+  ctx->split_m = ctx->epw;
+  ctx->split_o = ctx->epw;
+  if (cfg->split_obs_levels > 0) {
+    ctx->split_o = 1;
+    while (ctx->split_o * 2 <= cfg->split_obs_levels && ctx->split_o * 2 <= ctx->split_m) ctx->split_o *= 2;
+  }
+  ctx->split_groups = (cfg->batch + ctx->split_m - 1) / ctx->split_m;
+  ctx->split_lds_wave = lds_for(ctx->split_o);
 
   const size_t rows = (size_t)ctx->B_pad * ctx->S;
   struct { void** p; size_t n; } allocs[] = {
@@ -353,8 +372,12 @@ int pcgrl_step(pcgrl_ctx* ctx, const int32_t* actions, uint8_t* obs, float* rewa
   a.obs = obs;
   a.reward = reward;
   a.done = done;
-  if (obs && ctx->split)
+  if (obs && ctx->split) {
+    auto lg2 = [](int v) { return v == 4 ? 2 : v == 2 ? 1 : 0; };
+    a.envs_per_wave_log2 = lg2(ctx->split_m) | (lg2(ctx->split_o) << 8);
+    a.obs_lds_words = (int32_t)(ctx->split_lds_wave / 4);
     return dispatch<LaunchSplit>(ctx->S, ctx->cfg.problem, ctx, a, static_cast<hipStream_t>(stream));
+  }
   return dispatch<LaunchStep>(ctx->S, ctx->cfg.problem, ctx, a, static_cast<hipStream_t>(stream));
 }
 

@@ -52,7 +52,8 @@ struct KArgs {
   uint32_t* targets; // [B_pad][16], lo | hi << 16 (ranges are clamped to 0..65535)
   const int32_t* actions;
   int32_t B, plane_stride;
-  int32_t envs_per_wave_log2;  // distinct levels per wavefront = 1 << this; at most 64 / S
+  int32_t envs_per_wave_log2;  // bits 0-7: log2 of the distinct levels per wavefront (at most 64 / S);
+                               // bits 8-15, split step only: the same for an observation wavefront
   int32_t use_frozen;     // 0: no level of this context has a pinpoint cell; bit 1: a step needs the pinpoint rows (they are shown in the observation)
   uint8_t* obs;
   float* reward;
@@ -68,6 +69,7 @@ struct KArgs {
   int32_t flags;          // init kernel only
   int32_t rollout_steps;  // rollout kernel: steps per launch
   int32_t obs_slots;      // rollout kernel: step t writes observation slot t % obs_slots
+  int32_t obs_lds_words;  // split step: LDS words of one observation wavefront's staging area
   uint32_t cdf[8];
   float weights[kMaxMetrics];
   int32_t target_lo[kMaxMetrics], target_hi[kMaxMetrics];
@@ -735,12 +737,13 @@ template <int S> struct WaveMap {
   bool valid, primary;
   Slot sl;
   uint32_t* lds;
-  // One workgroup per wavefront's worth of levels; the grid has exactly that many workgroups.
-  __device__ __forceinline__ void init(const KArgs& a, const Lanes<S>& L, uint32_t* lds_all) {
+  // Wavefront number `wave_` of a launch whose wavefronts hold 1 << lg_ levels each.  (Without a
+  // split there is one workgroup per wavefront's worth of levels and exactly that many workgroups.)
+  __device__ __forceinline__ void init(const KArgs& a, const Lanes<S>& L, uint32_t* lds_, int wave_, int lg_) {
     constexpr int G = 64 / S;
-    wave = (int)blockIdx.x;
-    lds = lds_all;
-    const int lg = G == 1 ? 0 : a.envs_per_wave_log2;  // levels per wavefront = 1 << lg
+    wave = wave_;
+    lds = lds_;
+    const int lg = G == 1 ? 0 : lg_;  // levels per wavefront = 1 << lg
     const int epw = 1 << lg;
     sl.copies = G >> lg;
     sl.slot = L.g & (epw - 1);
@@ -750,7 +753,7 @@ template <int S> struct WaveMap {
     env = env0 + sl.slot;
     valid = env < a.B;
     primary = valid && sl.copy == 0;
-    envl = valid ? env : env0;  // an index that is always safe to load from
+    envl = valid ? env : min(env0, a.B - 1);  // an index that is always safe to load from
   }
 };
 
@@ -776,7 +779,7 @@ __global__ __launch_bounds__(64) void init_kernel(KArgs a) {
   extern __shared__ uint32_t lds_all[];
   Lanes<S> L;
   WaveMap<S> wm;
-  wm.init(a, L, lds_all);
+  wm.init(a, L, lds_all, (int)blockIdx.x, a.envs_per_wave_log2 & 0xff);
   W* planes = reinterpret_cast<W*>(a.planes);
   W* frozen = reinterpret_cast<W*>(a.frozen);
   const size_t ridx = (size_t)wm.envl * S + L.y;
@@ -843,7 +846,7 @@ __global__ __launch_bounds__(64) void exact_diameter_kernel(KArgs a, int32_t* ou
   extern __shared__ uint32_t lds_all[];
   Lanes<S> L;
   WaveMap<S> wm;
-  wm.init(a, L, lds_all);
+  wm.init(a, L, lds_all, (int)blockIdx.x, a.envs_per_wave_log2 & 0xff);
   const W* planes = reinterpret_cast<const W*>(a.planes);
   const size_t ridx = (size_t)wm.envl * S + L.y;
   W p[PR::P];
@@ -872,6 +875,10 @@ template <int S, int PROBLEM>
 __device__ __forceinline__ void obs_wave_step(const KArgs& a, const Lanes<S>& L, const WaveMap<S>& wm) {
   using W = typename RowWord<S>::T;
   using PR = Prob<PROBLEM>;
+  if (wm.env0 >= a.B) {  // the batch ends inside this workgroup: only the barrier is owed
+    __syncthreads();
+    return;
+  }
   const W* planes = reinterpret_cast<const W*>(a.planes);
   const size_t ridx = (size_t)wm.envl * S + L.y;
   W p[PR::P];
@@ -947,7 +954,7 @@ __device__ __forceinline__ void obs_wave_step(const KArgs& a, const Lanes<S>& L,
 // steps (pcgrl_rollout) during which the levels never leave the registers: per step only the
 // action is read and the observation, reward and done flag are written.
 template <int S, int PROBLEM, int MODE>
-__global__ __launch_bounds__(MODE == kModeSplit ? 128 : 64) void step_kernel(KArgs a) {
+__global__ __launch_bounds__(MODE == kModeSplit ? 320 : 64) void step_kernel(KArgs a) {
   using W = typename RowWord<S>::T;
   using PR = Prob<PROBLEM>;
   constexpr bool ROLL = MODE == kModeRollout, SPLIT = MODE == kModeSplit;
@@ -957,12 +964,17 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 128 : 64) void step_kernel(KAr
                "s"(a.actions), "s"(a.B), "s"(a.plane_stride), "s"(a.envs_per_wave_log2), "s"(a.use_frozen));
   Lanes<S> L;
   WaveMap<S> wm;
-  wm.init(a, L, lds_all);
+  wm.init(a, L, lds_all, (int)blockIdx.x, a.envs_per_wave_log2 & 0xff);
   // SPLIT: the workgroup is two wavefronts on the same levels; wavefront 0 does the metrics, the
   // reward and the state stores (the code below, without its observation parts), wavefront 1 the
   // observation; both load the same (old) state
   if constexpr (SPLIT) {
-    if (__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) == 1) {
+    // wavefront 0 of the workgroup computes the metrics of 1 << lg levels; each further wavefront
+    // writes the observations of 1 << lgo of them (a copy of the level in every spare lane group)
+    const int wid = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    if (wid != 0) {
+      const int lg = a.envs_per_wave_log2 & 0xff, lgo = (a.envs_per_wave_log2 >> 8) & 0xff;
+      wm.init(a, L, lds_all + (wid - 1) * a.obs_lds_words, ((int)blockIdx.x << (lg - lgo)) + wid - 1, lgo);
       obs_wave_step<S, PROBLEM>(a, L, wm);
       __builtin_amdgcn_endpgm();  // (not a return: the two paths must not meet again, or the
                                   // compiler makes this one wait for the other one's loads)

@@ -56,17 +56,22 @@ SMALL = [
 ]
 
 
-@pytest.mark.parametrize("lpw,split", [(0, 0), (2, 1), (4, 2), (1, 1)],
-                         ids=["auto", "lpw2-unsplit", "lpw4-split", "lpw1-unsplit"])
+@pytest.mark.parametrize("lpw,split,olv", [(0, 0, 0), (2, 1, 0), (4, 2, 0), (1, 1, 0), (4, 2, 2), (4, 2, 1), (2, 2, 1)],
+                         ids=["auto", "lpw2-unsplit", "lpw4-split", "lpw1-unsplit", "lpw4-split-obs2",
+                              "lpw4-split-obs1", "lpw2-split-obs1"])
 @pytest.mark.parametrize("label,cfg,steps,extra", SMALL, ids=[s[0] for s in SMALL])
-def test_small_configs_every_step(label, cfg, steps, extra, lpw, split):
+def test_small_configs_every_step(label, cfg, steps, extra, lpw, split, olv):
     """lpw = levels packed into one wavefront (automatic = 1 at these batch sizes, 2, as many as
-    the size class takes); split = one wavefront per level group, or a metrics wavefront and an
-    observation wavefront (automatic = split at these batch sizes)."""
-    if lpw > 1 and max(cfg["max_h"], cfg["max_w"]) > 32:
+    the size class takes); split = one wavefront per level group, or a metrics wavefront and
+    observation wavefronts (automatic = split at these batch sizes); olv = levels per observation
+    wavefront of a split step (0 = as many as the metrics wavefront holds)."""
+    side = max(cfg["max_h"], cfg["max_w"])
+    if lpw > 1 and side > 32:
         pytest.skip("a 64-row level fills the wavefront")
-    run_parity(dict(cfg, levels_per_wave=lpw, split_step=split), steps,
-               label=f"{label} lpw={lpw} split={split}", **extra)
+    if olv and lpw > 2 and side > 16:
+        pytest.skip("the same shape as lpw2-split-obs1 in this size class")
+    run_parity(dict(cfg, levels_per_wave=lpw, split_step=split, split_obs_levels=olv), steps,
+               label=f"{label} lpw={lpw} split={split} obs levels={olv}", **extra)
 
 
 @pytest.mark.parametrize("mode", [1, 2, 3], ids=["cached", "non-temporal", "write-through"])
@@ -234,7 +239,7 @@ def test_argument_errors_are_reported_not_raised_by_the_gpu():
     bad = wl.workload("maze16", batch=4)
     for field, val in (("obs_w", 64), ("max_h", 65), ("batch", 0), ("problem", 3), ("n_frozen", 9),
                        ("min_h", 17), ("max_steps", 0), ("pad_mode", 2), ("levels_per_wave", 5),
-                       ("split_step", 3), ("obs_store_mode", 4)):
+                       ("split_step", 3), ("obs_store_mode", 4), ("split_obs_levels", 5)):
         with pytest.raises(binding.PcgrlError):
             binding.Pcgrl(dict(bad, **{field: val}), 0)
     env = binding.Pcgrl(bad, 0)
