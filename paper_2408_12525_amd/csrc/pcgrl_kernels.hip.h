@@ -1066,6 +1066,7 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 320 : 64) void step_kernel(KAr
   bool planes_dirty = false, fz_dirty = false;  // ROLL: what has to be written back at the end
   bool metrics_dirty = false, targets_dirty = false;
   W next_fz_row = 0;
+  uint32_t next_cell_frozen = 0;
 
   const int nsteps = ROLL ? a.rollout_steps : 1;
   for (int step = 0; step < nsteps; ++step) {
@@ -1250,6 +1251,12 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 320 : 64) void step_kernel(KAr
     }
 
     // ---- per-step outputs
+    // (a single step takes the pinpoint flag of the next cell out of its loaded row here, before
+    // the stores below are issued: waiting for that load later would wait for these stores too)
+    if constexpr (!ROLL) {
+      next_cell_frozen = (uint32_t)((next_fz_row >> qx) & 1);
+      asm volatile("" : "+v"(next_cell_frozen));
+    }
     if (wm.primary && L.y == 0) {
       if (a.reward) a.reward[(size_t)step * a.B + wm.env] = reward;
       if (a.done) a.done[(size_t)step * a.B + wm.env] = done ? 1 : 0;
@@ -1282,7 +1289,7 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 320 : 64) void step_kernel(KAr
     er.w = (uint8_t)w;
     er.py = (uint8_t)py;
     er.px = (uint8_t)px;
-    er.cell_frozen = (uint32_t)((next_fz_row >> px) & 1);
+    er.cell_frozen = ROLL ? (uint32_t)((next_fz_row >> px) & 1) : next_cell_frozen;
     a.env[wm.env] = er;
     if (metrics_dirty) store_metrics<S, PROBLEM>(a.metrics + (size_t)wm.env * kMaxMetrics, mo);
     if (targets_dirty) {
