@@ -1254,8 +1254,10 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 320 : 64) void step_kernel(KAr
     // (a single step takes the pinpoint flag of the next cell out of its loaded row here, before
     // the stores below are issued: waiting for that load later would wait for these stores too)
     if constexpr (!ROLL) {
-      next_cell_frozen = (uint32_t)((next_fz_row >> qx) & 1);
-      asm volatile("" : "+v"(next_cell_frozen));
+      if (a.use_frozen) {  // (a branch, so that contexts without pinpoints skip the wait as well)
+        next_cell_frozen = (uint32_t)((next_fz_row >> qx) & 1);
+        asm volatile("" : "+v"(next_cell_frozen));
+      }
     }
     if (wm.primary && L.y == 0) {
       if (a.reward) a.reward[(size_t)step * a.B + wm.env] = reward;
