@@ -988,8 +988,15 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 320 : 64) void step_kernel(KAr
   constexpr bool ROLL = MODE == kModeRollout, SPLIT = MODE == kModeSplit;
   extern __shared__ uint32_t lds_all[];
   // fetch the head of the argument block in one go; the rest arrives while the loads are in flight
-  asm volatile("" ::"s"(a.planes), "s"(a.frozen), "s"(a.env), "s"(a.metrics), "s"(a.targets),
-               "s"(a.actions), "s"(a.B), "s"(a.plane_stride), "s"(a.envs_per_wave_log2), "s"(a.use_frozen));
+  if constexpr (!SPLIT)
+    asm volatile("" ::"s"(a.planes), "s"(a.frozen), "s"(a.env), "s"(a.metrics), "s"(a.targets),
+                 "s"(a.actions), "s"(a.B), "s"(a.plane_stride), "s"(a.envs_per_wave_log2), "s"(a.use_frozen));
+  else  // (the split kernel's wavefronts are lean enough to hold what the observation path reads, too)
+    asm volatile("" ::"s"(a.planes), "s"(a.frozen), "s"(a.env), "s"(a.metrics), "s"(a.targets),
+                 "s"(a.actions), "s"(a.B), "s"(a.plane_stride), "s"(a.envs_per_wave_log2), "s"(a.use_frozen),
+                 "s"(a.obs), "s"(a.env_obs_bytes), "s"(a.obs_packed), "s"(a.obs_w), "s"(a.obs_lds_words),
+                 "s"(a.max_steps), "s"(a.max_changes), "s"(a.pos_mode), "s"(a.autoreset), "s"(a.pad_mode),
+                 "s"(a.obs_frozen_channel), "s"(a.stream_obs));
   Lanes<S> L;
   WaveMap<S> wm;
   wm.init(a, L, lds_all, (int)blockIdx.x, a.envs_per_wave_log2 & 0xff);
