@@ -69,7 +69,8 @@ extern "C" {
 
 #define PCGRL_SPLIT_AUTO 0 /* decide from the number of wavefronts the batch needs */
 #define PCGRL_SPLIT_OFF 1  /* one wavefront per level group does the whole step */
-#define PCGRL_SPLIT_ON 2   /* pcgrl_step runs a metrics wavefront and an observation wavefront */
+#define PCGRL_SPLIT_ON 2   /* pcgrl_step and pcgrl_rollout run a metrics wavefront and observation
+                              wavefronts per group of levels (each holds the levels itself) */
 
 #define PCGRL_OBS_ONEHOT_U8 0 /* uint8 [batch][C][obs_w][obs_w], one byte per one-hot cell */
 #define PCGRL_OBS_PACKED 1    /* the same cells as bits: uint8 [batch][ceil(C*obs_w*obs_w / 8)], cell j of

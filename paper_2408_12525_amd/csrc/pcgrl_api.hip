@@ -18,6 +18,9 @@ struct pcgrl_ctx {
   int epw;  // distinct levels per wavefront (a divisor of G)
   size_t word_bytes;
   size_t lds_bytes;  // per wavefront
+  int split_roll;    // pcgrl_rollout with observations does the same, with its own shape:
+  int roll_m, roll_o, roll_groups;
+  size_t roll_lds_wave;
   int split;         // pcgrl_step with an observation uses the metrics | observation kernel, with
   int split_m, split_o, split_groups;  // this many levels per metrics / observation wavefront and workgroups
   size_t split_lds_wave;  // LDS bytes of one observation wavefront there
@@ -98,6 +101,14 @@ template <int S, int PROBLEM> struct LaunchSplit {  // a metrics wavefront and i
     const int obs_waves = ctx->split_m / ctx->split_o;
     hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeSplit>), dim3(ctx->split_groups), dim3(64 * (1 + obs_waves)),
                        obs_waves * ctx->split_lds_wave, st, a);
+    return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
+  }
+};
+template <int S, int PROBLEM> struct LaunchRolloutSplit {
+  static int run(const pcgrl_ctx* ctx, const KArgs& a, hipStream_t st) {
+    const int obs_waves = ctx->roll_m / ctx->roll_o;
+    hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeRolloutSplit>), dim3(ctx->roll_groups),
+                       dim3(64 * (1 + obs_waves)), obs_waves * ctx->roll_lds_wave, st, a);
     return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
   }
 };
@@ -243,8 +254,13 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   // up to 2048 wavefronts and of 7 % for 32x32 levels with a 12 KB observation, a few percent
   // either way elsewhere.
   ctx->split = ((ctx->S == 16 && ctx->nwaves <= 2048) || (ctx->S == 32 && E >= 8192 && ctx->nwaves <= 8192)) ? 1 : 0;
-  if (cfg->split_step == PCGRL_SPLIT_OFF) ctx->split = 0;
-  if (cfg->split_step == PCGRL_SPLIT_ON) ctx->split = 1;
+  // A rollout split the same way (each wavefront keeps its own copy of the level for all the
+  // steps): measured -35 % per step for 16x16 levels at batches of 64 and 1024, within a few
+  // percent either way from 4096 on (100 steps per launch); -6 % for 64x64 levels; within +-8 %
+  // either way for 32x32 levels.
+  ctx->split_roll = ((ctx->S == 16 && cfg->batch <= 2048) || (ctx->S == 64 && cfg->batch <= 8192)) ? 1 : 0;
+  if (cfg->split_step == PCGRL_SPLIT_OFF) ctx->split = ctx->split_roll = 0;
+  if (cfg->split_step == PCGRL_SPLIT_ON) ctx->split = ctx->split_roll = 1;
   // Shape of the split step: one metrics wavefront carries as many levels as the explicit choice
   // (or the automatic one above) says, and the observation can be shared out over several
   // wavefronts of split_o levels each (measured: within 3 % of one observation wavefront, which
@@ -257,6 +273,16 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   }
   ctx->split_groups = (cfg->batch + ctx->split_m - 1) / ctx->split_m;
   ctx->split_lds_wave = lds_for(ctx->split_o);
+  // The split rollout is bound by instruction issue sooner than a single step is by its chain:
+  // it packs as many levels into a wavefront as leave about a thousand workgroups (measured).
+  ctx->roll_m = ctx->G;
+  while (ctx->roll_m > 1 && (cfg->batch + ctx->roll_m - 1) / ctx->roll_m < 1024) ctx->roll_m /= 2;
+  ctx->roll_o = (ctx->roll_m == 4 && cfg->batch / ctx->roll_m >= 4096) ? 2 : ctx->roll_m;
+  if (cfg->levels_per_wave > 0) ctx->roll_m = ctx->roll_o = ctx->split_m;
+  if (cfg->split_obs_levels > 0) ctx->roll_o = ctx->split_o < ctx->roll_m ? ctx->split_o : ctx->roll_m;
+  ctx->roll_groups = (cfg->batch + ctx->roll_m - 1) / ctx->roll_m;
+  ctx->roll_lds_wave = lds_for(ctx->roll_o);
+  if (ctx->roll_lds_wave * (ctx->roll_m / ctx->roll_o) > 64 * 1024) ctx->split_roll = 0;
 
   const size_t rows = (size_t)ctx->B_pad * ctx->S;
   struct { void** p; size_t n; } allocs[] = {
@@ -395,6 +421,12 @@ int pcgrl_rollout(pcgrl_ctx* ctx, const int32_t* actions, int32_t n_steps, uint8
   a.rollout_steps = n_steps;
   a.obs_slots = obs ? obs_slots : 1;
   a.stream_obs = ctx->store_roll;
+  if (obs && ctx->split_roll) {
+    auto lg2 = [](int v) { return v == 4 ? 2 : v == 2 ? 1 : 0; };
+    a.envs_per_wave_log2 = lg2(ctx->roll_m) | (lg2(ctx->roll_o) << 8);
+    a.obs_lds_words = (int32_t)(ctx->roll_lds_wave / 4);
+    return dispatch<LaunchRolloutSplit>(ctx->S, ctx->cfg.problem, ctx, a, static_cast<hipStream_t>(stream));
+  }
   return dispatch<LaunchRollout>(ctx->S, ctx->cfg.problem, ctx, a, static_cast<hipStream_t>(stream));
 }
 

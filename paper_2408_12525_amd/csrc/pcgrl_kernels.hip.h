@@ -28,8 +28,10 @@ enum : int { kRegionsIncremental = 0, kRegionsRecount = 1 };
 enum : int { kStoreCached = 0, kStoreStream = 1, kStoreThrough = 2 };
 enum : int { kInitGenerate = 1, kInitMetrics = 2, kInitObs = 4, kInitTargets = 8 };
 // step kernel variants: one step per launch; the same with the work of a wavefront split over
-// two (a metrics wavefront and an observation wavefront per workgroup); n steps per launch
-enum : int { kModeStep = 0, kModeSplit = 1, kModeRollout = 2 };
+// two (a metrics wavefront and an observation wavefront per workgroup); n steps per launch; n steps
+// per launch split the same way
+// (split variants: a metrics wavefront and observation wavefronts per workgroup)
+enum : int { kModeStep = 0, kModeSplit = 1, kModeRollout = 2, kModeRolloutSplit = 3 };
 
 // Per-environment scalars, 32 bytes, read and written as two 16-byte words.
 struct __attribute__((aligned(16))) EnvRec {
@@ -978,14 +980,108 @@ __device__ __forceinline__ void obs_wave_step(const KArgs& a, const Lanes<S>& L,
   observe<S, PROBLEM, true>(a, L, wm, pl, p, fz, inside, qy, qx);
 }
 
+// The observation wavefront of a split rollout.  It needs nothing from the metrics wavefront: what
+// an observation shows -- the edited level, the agent's next cell, a restarted episode -- follows
+// from the loaded state, the seeds and the action stream alone, so this wavefront carries its own
+// copy of the level through all the steps and only writes observations.
+template <int S, int PROBLEM>
+__device__ __forceinline__ void obs_wave_rollout(const KArgs& a, const Lanes<S>& L, const WaveMap<S>& wm) {
+  using W = typename RowWord<S>::T;
+  using PR = Prob<PROBLEM>;
+  if (wm.env0 >= a.B) {  // the batch ends inside this workgroup: only the barrier is owed
+    __syncthreads();
+    return;
+  }
+  const W* planes = reinterpret_cast<const W*>(a.planes);
+  const size_t ridx = (size_t)wm.envl * S + L.y;
+  W p[PR::P];
+#pragma unroll
+  for (int i = 0; i < PR::P; ++i) p[i] = planes[(size_t)i * a.plane_stride + ridx];
+  W fz = reinterpret_cast<const W*>(a.frozen)[ridx];
+  const uint4* erp = reinterpret_cast<const uint4*>(a.env + wm.envl);
+  const uint4 er0 = erp[0], er1 = erp[1];
+  int act = a.actions[wm.envl];
+  __builtin_amdgcn_sched_barrier(0);
+  __syncthreads();  // (the metrics wavefront stores the final state only after this)
+
+  int h = (int)(er0.x & 0xffu), w = (int)((er0.x >> 8) & 0xffu);
+  int py = (int)((er0.x >> 16) & 0xffu), px = (int)(er0.x >> 24);
+  int t = (int)er0.y, n_changes = (int)er0.z, episode = (int)er0.w;
+  uint64_t key = (uint64_t)er1.x | ((uint64_t)er1.y << 32);
+  W inside = inside_row<W>(L.y, h, w);
+  const int nsteps = a.rollout_steps;
+  for (int step = 0; step < nsteps; ++step) {
+    int act_next = -1;
+    if (step + 1 < nsteps) act_next = a.actions[(size_t)(step + 1) * a.B + wm.envl];
+    // the edit (the old tile matters only when changes are counted against a budget)
+    const bool at_row = L.y == py;
+    const bool is_frozen = L.gany(at_row && ((fz >> px) & 1));
+    const bool may_write = wm.valid && act >= 0 && act < PR::K && !is_frozen;
+    t += 1;
+    bool done = t >= a.max_steps;
+    if (a.max_changes > 0) {
+      int old_code = 0;
+#pragma unroll
+      for (int i = 0; i < PR::P; ++i) old_code |= (L.gany(at_row && ((p[i] >> px) & 1)) ? 1 : 0) << i;
+      n_changes += (may_write && act != old_code) ? 1 : 0;
+      done = done || n_changes >= a.max_changes;
+    }
+    if (may_write && at_row) {
+#pragma unroll
+      for (int i = 0; i < PR::P; ++i) p[i] = (p[i] & ~((W)1 << px)) | ((W)((act >> i) & 1) << px);
+    }
+    int qy = py, qx = px;
+    if (a.pos_mode == kPosScan) {
+      qx += 1;
+      if (qx >= w) {
+        qx = 0;
+        qy += 1;
+        if (qy >= h) qy = 0;
+      }
+    } else {
+      uint64_t u = draw(key, 3, (uint32_t)t);
+      qy = below((uint32_t)(u >> 32), h);
+      qx = below((uint32_t)u, w);
+    }
+    const bool restart = wm.valid && done && a.autoreset != 0;
+    if (wave_any<S>(restart)) {
+      const KArgs& ra = cold_args();
+      W np[PR::P], nfz;
+      int nh, nw, npy, npx;
+      uint64_t nkey = env_key(ra.seed, (uint64_t)wm.envl, (uint64_t)(episode + 1));
+      begin_episode<S, PROBLEM>(ra, L, nkey, np, nfz, nh, nw, npy, npx);
+      if (restart) {
+#pragma unroll
+        for (int i = 0; i < PR::P; ++i) p[i] = np[i];
+        fz = nfz;
+        h = nh;
+        w = nw;
+        inside = inside_row<W>(L.y, nh, nw);
+        qy = npy;
+        qx = npx;
+        key = nkey;
+        episode += 1;
+        t = 0;
+        n_changes = 0;
+      }
+    }
+    uint8_t* obs = a.obs + (size_t)(step % a.obs_slots) * (size_t)a.B * (size_t)a.env_obs_bytes;
+    observe<S, PROBLEM>(a, L, wm, obs_plan(a, L.lane, wm.sl, obs, wm.env0, wm.nvalid), p, fz, inside, qy, qx);
+    py = qy;
+    px = qx;
+    act = act_next;
+  }
+}
+
 // One environment step of every level (pcgrl_step), or, with ROLL, `rollout_steps` consecutive
 // steps (pcgrl_rollout) during which the levels never leave the registers: per step only the
 // action is read and the observation, reward and done flag are written.
 template <int S, int PROBLEM, int MODE>
-__global__ __launch_bounds__(MODE == kModeSplit ? 320 : 64) void step_kernel(KArgs a) {
+__global__ __launch_bounds__(MODE == kModeSplit || MODE == kModeRolloutSplit ? 320 : 64) void step_kernel(KArgs a) {
   using W = typename RowWord<S>::T;
   using PR = Prob<PROBLEM>;
-  constexpr bool ROLL = MODE == kModeRollout, SPLIT = MODE == kModeSplit;
+  constexpr bool ROLL = MODE == kModeRollout || MODE == kModeRolloutSplit;
+  constexpr bool SPLIT = MODE == kModeSplit || MODE == kModeRolloutSplit;
   extern __shared__ uint32_t lds_all[];
   // fetch the head of the argument block in one go; the rest arrives while the loads are in flight
   if constexpr (!SPLIT)
@@ -1010,7 +1106,8 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 320 : 64) void step_kernel(KAr
     if (wid != 0) {
       const int lg = a.envs_per_wave_log2 & 0xff, lgo = (a.envs_per_wave_log2 >> 8) & 0xff;
       wm.init(a, L, lds_all + (wid - 1) * a.obs_lds_words, ((int)blockIdx.x << (lg - lgo)) + wid - 1, lgo);
-      obs_wave_step<S, PROBLEM>(a, L, wm);
+      if constexpr (ROLL) obs_wave_rollout<S, PROBLEM>(a, L, wm);
+      else obs_wave_step<S, PROBLEM>(a, L, wm);
       __builtin_amdgcn_endpgm();  // (not a return: the two paths must not meet again, or the
                                   // compiler makes this one wait for the other one's loads)
     }
@@ -1083,7 +1180,7 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 320 : 64) void step_kernel(KAr
       if (step + 1 < nsteps) act_next = a.actions[(size_t)(step + 1) * a.B + wm.envl];
     }
     uint8_t* obs = a.obs;
-    if constexpr (ROLL) {
+    if constexpr (ROLL && !SPLIT) {
       if (obs != nullptr) {
         obs += (size_t)(step % a.obs_slots) * (size_t)a.B * (size_t)a.env_obs_bytes;
         pl = obs_plan(a, L.lane, wm.sl, obs, wm.env0, wm.nvalid);

@@ -317,12 +317,15 @@ ROLLOUTS = [
 ]
 
 
+@pytest.mark.parametrize("split,olv", [(1, 0), (2, 0), (2, 1)], ids=["one-wavefront", "split", "split-obs1"])
 @pytest.mark.parametrize("label,cfg,T,slots", ROLLOUTS, ids=[r[0] for r in ROLLOUTS])
-def test_rollout_equals_the_same_steps_one_by_one(label, cfg, T, slots):
+def test_rollout_equals_the_same_steps_one_by_one(label, cfg, T, slots, split, olv):
     """pcgrl_rollout against the oracle stepped T times (every observation slot that survives,
     every reward and done flag, final state and metrics), with auto-resets inside the rollout, and
-    against T calls of pcgrl_step."""
-    print(f"[rollout] {label} T={T} slots={slots}", flush=True)
+    against T calls of pcgrl_step.  split: the levels stay in one wavefront for the whole rollout,
+    or in a metrics wavefront and observation wavefronts that each carry their own copy."""
+    cfg = dict(cfg, split_step=split, split_obs_levels=olv)
+    print(f"[rollout] {label} T={T} slots={slots} split={split} obs levels={olv}", flush=True)
     dev = torch.device("cuda", 0)
     B = cfg["batch"]
     acts_np = wl.random_actions(cfg, 8, T, bad_fraction=0.03)
