@@ -919,13 +919,16 @@ __device__ __forceinline__ void obs_wave_step(const KArgs& a, const Lanes<S>& L,
   const uint4* erp = reinterpret_cast<const uint4*>(a.env + wm.envl);
   const uint4 er0 = erp[0], er1 = erp[1];
   const int act = a.actions[wm.envl];
+  // the barrier as soon as the loads are issued (the metrics wavefront waits there for nothing
+  // else), fenced off so that no use of a loaded value, with its wait, moves in front of it
+  __builtin_amdgcn_sched_barrier(0);
+  __syncthreads();
   __builtin_amdgcn_sched_barrier(0);
   if (!(a.use_frozen & 2)) fz = 0;
   ObsPlan pl = obs_plan(a, L.lane, wm.sl, a.obs, wm.env0, wm.nvalid);
   obs_plan_pin(pl);
   obs_clear(wm.lds, L.lane, pl);
   __builtin_amdgcn_sched_barrier(0);
-  __syncthreads();
 
   int h = (int)(er0.x & 0xffu), w = (int)((er0.x >> 8) & 0xffu);
   const int py = (int)((er0.x >> 16) & 0xffu), px = (int)(er0.x >> 24);
@@ -1003,6 +1006,7 @@ __device__ __forceinline__ void obs_wave_rollout(const KArgs& a, const Lanes<S>&
   int act = a.actions[wm.envl];
   __builtin_amdgcn_sched_barrier(0);
   __syncthreads();  // (the metrics wavefront stores the final state only after this)
+  __builtin_amdgcn_sched_barrier(0);
 
   int h = (int)(er0.x & 0xffu), w = (int)((er0.x >> 8) & 0xffu);
   int py = (int)((er0.x >> 16) & 0xffu), px = (int)(er0.x >> 24);
