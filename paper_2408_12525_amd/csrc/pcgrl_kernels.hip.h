@@ -162,10 +162,46 @@ template <int S> struct Lanes {
       return ((uint64_t)hi << 32) | lo;
     }
   }
-  // the four-neighbour dilation of a cell set (the set itself included), not yet masked
+  // The four-neighbour dilation of a cell set (the set itself included), not yet masked.
+  // Written out instruction by instruction so that every lane shift rides on an OR (the compiler's
+  // three-operand ORs cannot take a lane-shifted operand and need a separate move for each, and it
+  // masks the group boundary of 32-row levels with two selects).  A lane-shifted read must come at
+  // least two instructions after the write of any register the instruction uses: f is written
+  // before the block, the accumulators two instructions before they are used again.
   __device__ __forceinline__ W dilate(W f) const {
-    return f | (W)(f << 1) | (W)(f >> 1) | from_above(f) | from_below(f);
+    if constexpr (S == 16) {
+      uint32_t t, u;
+      asm("v_lshrrev_b32 %0, 1, %2\n\t"
+          "v_lshl_or_b32 %0, %2, 1, %0\n\t"
+          "v_or_b32_dpp %1, %2, %2 row_shr:1 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+          "s_nop 0\n\t"
+          "v_or_b32_dpp %0, %2, %0 row_shl:1 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+          : "=&v"(t), "=&v"(u)
+          : "v"(f));
+      return t | u;
+    } else if constexpr (S == 32) {
+      // a shift inside each row of 16 lanes, then the step across the boundary between the two
+      // rows of one level only (rows 1 and 3 take from below them, rows 0 and 2 from above them);
+      // the second step repeats values the first has already ORed in, which does no harm
+      uint32_t t, u;
+      asm("v_lshrrev_b32 %0, 1, %2\n\t"
+          "v_lshl_or_b32 %0, %2, 1, %0\n\t"
+          "v_or_b32_dpp %1, %2, %2 row_shr:1 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+          "s_nop 0\n\t"
+          "v_or_b32_dpp %0, %2, %0 row_shl:1 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+          "v_or_b32_dpp %1, %2, %1 wave_shr:1 row_mask:0xa bank_mask:0xf bound_ctrl:1\n\t"
+          "s_nop 0\n\t"
+          "v_or_b32_dpp %0, %2, %0 wave_shl:1 row_mask:0x5 bank_mask:0xf bound_ctrl:1"
+          : "=&v"(t), "=&v"(u)
+          : "v"(f));
+      return t | u;
+    } else {
+      // (for 64-row levels the same treatment was measured and is slower than the compiler's code)
+      return f | (W)(f << 1) | (W)(f >> 1) | from_above(f) | from_below(f);
+    }
   }
+  // one breadth-first layer inside the cell set r
+  __device__ __forceinline__ W grow(W f, W r) const { return dilate(f) & r; }
   // bits of a wave ballot that belong to this lane's group, moved down to bit 0
   __device__ __forceinline__ uint64_t gbits(uint64_t ballot) const {
     if constexpr (S == 64) return ballot;
@@ -244,9 +280,9 @@ __device__ __forceinline__ int sweep(const Lanes<S>& L, typename RowWord<S>::T s
   W V = seed, lastN = seed;
   int it = 0, last_it = 0;
   for (;;) {  // two layers per convergence test
-    W V1 = L.dilate(V) & pass;
+    W V1 = L.grow(V, pass);
     W N1 = V1 ^ V;
-    W V2 = L.dilate(V1) & pass;
+    W V2 = L.grow(V1, pass);
     W N2 = V2 ^ V1;
     if (N1 != 0) {
       lastN = N1;
@@ -289,11 +325,11 @@ __device__ __forceinline__ int nearest(const Lanes<S>& L, typename RowWord<S>::T
   int d = -1, it = 0;
   reached = 0;
   for (;;) {  // two layers per trip
-    W V1 = L.dilate(V) & pass;
-    W V2 = L.dilate(V1) & pass;
+    W V1 = L.grow(V, pass);
+    W V2 = L.grow(V1, pass);
     uint64_t h1 = L.gbits(__builtin_amdgcn_ballot_w64((V1 & tgt) != 0));
     uint64_t h2 = L.gbits(__builtin_amdgcn_ballot_w64((V2 & tgt) != 0));
-    bool ch = V2 != V;
+    bool ch = V2 != V1;  // a second layer that adds nothing means the flood is complete
     V = V2;
     if (d < 0 && h2 != 0) {  // the target set is hit in the first layer whenever h1 says so
       d = h1 != 0 ? it + 1 : it + 2;
@@ -320,13 +356,13 @@ __device__ __forceinline__ void nearest_two(const Lanes<S>& L, typename RowWord<
   d_b = -1;
   reached_a = 0;
   for (;;) {  // two layers per trip
-    W V1 = L.dilate(V) & pass;
-    W V2 = L.dilate(V1) & pass;
+    W V1 = L.grow(V, pass);
+    W V2 = L.grow(V1, pass);
     uint64_t a1 = L.gbits(__builtin_amdgcn_ballot_w64((V1 & tgt_a) != 0));
     uint64_t a2 = L.gbits(__builtin_amdgcn_ballot_w64((V2 & tgt_a) != 0));
     uint64_t b1 = L.gbits(__builtin_amdgcn_ballot_w64((V1 & tgt_b) != 0));
     uint64_t b2 = L.gbits(__builtin_amdgcn_ballot_w64((V2 & tgt_b) != 0));
-    bool ch = V2 != V;
+    bool ch = V2 != V1;
     V = V2;
     if (d_a < 0 && a2 != 0) {
       d_a = a1 != 0 ? it + 1 : it + 2;
@@ -357,8 +393,9 @@ __device__ __forceinline__ int regions_full(const Lanes<S>& L, typename RowWord<
     if (!wave_any<S>(V != 0)) break;
     count += L.gany(V != 0) ? 1 : 0;
     for (;;) {
-      W Vn = L.dilate(L.dilate(V) & R) & R;
-      bool ch = Vn != V;
+      W V1 = L.grow(V, R);
+      W Vn = L.grow(V1, R);
+      bool ch = Vn != V1;  // a second layer that adds nothing means the flood is complete
       V = Vn;
       if (!wave_any<S>(ch)) break;
     }
@@ -395,8 +432,9 @@ __device__ __forceinline__ int neighbour_components(const Lanes<S>& L, typename 
     W pw = go ? passw : (W)0;
     k += go ? 1 : 0;
     for (;;) {
-      W Vn = L.dilate(L.dilate(V) & pw) & pw;
-      bool ch = Vn != V;
+      W V1 = L.grow(V, pw);
+      W Vn = L.grow(V1, pw);
+      bool ch = Vn != V1;
       V = Vn;
       bool open = L.gany((U & ~V) != 0);  // some neighbour still unreached
       if (!open) {                        // everything met: this group is finished for good
