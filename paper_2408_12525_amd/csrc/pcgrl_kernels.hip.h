@@ -272,33 +272,56 @@ __device__ __forceinline__ W channel_row(const W (&p)[Prob<PROBLEM>::P], W insid
 
 // One sweep of the two-sweep diameter estimate: breadth-first layers from `seed` inside `pass`.
 // Returns the eccentricity of the seed and leaves in `last` the cells of the last layer
-// (the seed itself when nothing else is reachable).
+// (the seed itself when nothing else is reachable).  The loop advances two layers per trip and
+// only remembers, per lane, what the last pair of layers that reached the lane added; which of the
+// two layers was the last one is worked out after the loop with one more layer from the cells
+// known before that pair.
 template <int S>
 __device__ __forceinline__ int sweep(const Lanes<S>& L, typename RowWord<S>::T seed,
                                      typename RowWord<S>::T pass, typename RowWord<S>::T& last) {
   using W = typename RowWord<S>::T;
-  W V = seed, lastN = seed;
-  int it = 0, last_it = 0;
-  for (;;) {  // two layers per convergence test
+  W V = seed, added = seed;
+  int k = 0, k_last = 0;  // pairs done; the pair that last added cells in this lane
+  for (;;) {
     W V1 = L.grow(V, pass);
-    W N1 = V1 ^ V;
     W V2 = L.grow(V1, pass);
-    W N2 = V2 ^ V1;
-    if (N1 != 0) {
-      lastN = N1;
-      last_it = it + 1;
+    k += 1;
+    if (V2 != V) {
+      added = V2 ^ V;
+      k_last = k;
     }
-    if (N2 != 0) {
-      lastN = N2;
-      last_it = it + 2;
-    }
-    it += 2;
+    bool more = V2 != V1;  // a second layer that adds nothing means the flood is complete
     V = V2;
-    if (!wave_any<S>(N2 != 0)) break;
+    if (!wave_any<S>(more)) break;
   }
-  int d = L.gmax(last_it);
-  last = last_it == d ? lastN : (W)0;
-  return d;
+  const int kk = L.gmax(k_last);               // the last pair that added cells to the level
+  const W pair = k_last == kk ? added : (W)0;  // what it added
+  const W before = V & ~pair;
+  const W first = L.grow(before, pass) & ~before;
+  const W second = pair & ~first;
+  const bool two = L.gany(second != 0);
+  last = two ? second : first;
+  return kk == 0 ? 0 : 2 * kk - (two ? 0 : 1);
+}
+
+// The eccentricity alone.
+template <int S>
+__device__ __forceinline__ int eccentricity(const Lanes<S>& L, typename RowWord<S>::T seed,
+                                            typename RowWord<S>::T pass) {
+  using W = typename RowWord<S>::T;
+  W V = seed;
+  int k = 0, k1 = 0, k2 = 0;  // pairs done; the pairs whose first / second layer last reached this lane
+  for (;;) {
+    W V1 = L.grow(V, pass);
+    W V2 = L.grow(V1, pass);
+    k += 1;
+    if (V1 != V) k1 = k;
+    bool more = V2 != V1;
+    if (more) k2 = k;
+    V = V2;
+    if (!wave_any<S>(more)) break;
+  }
+  return L.gmax(max(2 * k2, 2 * k1 - 1));
 }
 
 // Binary domain, footnote: sweep from the first walkable cell x, then from the far end of the
@@ -310,8 +333,7 @@ __device__ __forceinline__ int two_sweep_diameter(const Lanes<S>& L, typename Ro
   W far;
   sweep<S>(L, x, pass, far);
   W y = first_cell<S>(L, far);
-  W unused;
-  return sweep<S>(L, y, pass, unused);
+  return eccentricity<S>(L, y, pass);
 }
 
 // Distance from a source set to the nearest cell of a target set, -1 if none is reachable.
@@ -436,12 +458,9 @@ __device__ __forceinline__ int neighbour_components(const Lanes<S>& L, typename 
       W Vn = L.grow(V1, pw);
       bool ch = Vn != V1;
       V = Vn;
-      bool open = L.gany((U & ~V) != 0);  // some neighbour still unreached
-      if (!open) {                        // everything met: this group is finished for good
-        U = 0;
-        V = 0;
-        pw = 0;
-      }
+      // a group whose neighbours are all reached is finished for good: whatever its flood still
+      // adds while other groups go on changes nothing below
+      bool open = L.gany((U & ~V) != 0);
       if (!wave_any<S>(ch && open)) break;
     }
     U &= ~V;
@@ -929,8 +948,7 @@ __global__ __launch_bounds__(64) void exact_diameter_kernel(KArgs a, int32_t* ou
     const W src = first_cell<S>(L, todo);
     if (!wave_any<S>(src != 0)) break;
     todo &= ~src;
-    W unused;
-    best = max(best, sweep<S>(L, src, pass, unused));
+    best = max(best, eccentricity<S>(L, src, pass));
   }
   if (wm.primary && L.y == 0) out[wm.env] = best;
 }
