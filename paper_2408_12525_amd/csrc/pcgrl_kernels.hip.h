@@ -269,6 +269,10 @@ __device__ __forceinline__ W channel_row(const W (&p)[Prob<PROBLEM>::P], W insid
 }
 
 // ------------------------------------------------------------------ metrics
+// Floods test for their end after every second layer at first and, after this many such trips,
+// after every fourth layer: most floods are over within a few layers, but the test and the jump
+// back cost about as much as three layers, which long floods need not pay every time.
+constexpr int kShortTrips = 2;
 
 // One sweep of the two-sweep diameter estimate: breadth-first layers from `seed` inside `pass`.
 // Returns the eccentricity of the seed and leaves in `last` the cells of the last layer
@@ -282,7 +286,7 @@ __device__ __forceinline__ int sweep(const Lanes<S>& L, typename RowWord<S>::T s
   using W = typename RowWord<S>::T;
   W V = seed, added = seed;
   int k = 0, k_last = 0;  // pairs done; the pair that last added cells in this lane
-  for (;;) {
+  auto pair_of_layers = [&]() {
     W V1 = L.grow(V, pass);
     W V2 = L.grow(V1, pass);
     k += 1;
@@ -290,9 +294,14 @@ __device__ __forceinline__ int sweep(const Lanes<S>& L, typename RowWord<S>::T s
       added = V2 ^ V;
       k_last = k;
     }
-    bool more = V2 != V1;  // a second layer that adds nothing means the flood is complete
     V = V2;
-    if (!wave_any<S>(more)) break;
+    return V2 != V1;  // a second layer that adds nothing means the flood is complete
+  };
+  bool more = true;
+  for (int n = 0; n < kShortTrips && more; ++n) more = wave_any<S>(pair_of_layers());
+  while (more) {  // (long floods test for the end every fourth layer only, as the region search does)
+    pair_of_layers();
+    more = wave_any<S>(pair_of_layers());
   }
   const int kk = L.gmax(k_last);               // the last pair that added cells to the level
   const W pair = k_last == kk ? added : (W)0;  // what it added
@@ -311,15 +320,21 @@ __device__ __forceinline__ int eccentricity(const Lanes<S>& L, typename RowWord<
   using W = typename RowWord<S>::T;
   W V = seed;
   int k = 0, k1 = 0, k2 = 0;  // pairs done; the pairs whose first / second layer last reached this lane
-  for (;;) {
+  auto pair_of_layers = [&]() {
     W V1 = L.grow(V, pass);
     W V2 = L.grow(V1, pass);
     k += 1;
     if (V1 != V) k1 = k;
-    bool more = V2 != V1;
-    if (more) k2 = k;
+    const bool grew = V2 != V1;
+    if (grew) k2 = k;
     V = V2;
-    if (!wave_any<S>(more)) break;
+    return grew;
+  };
+  bool more = true;
+  for (int n = 0; n < kShortTrips && more; ++n) more = wave_any<S>(pair_of_layers());
+  while (more) {
+    pair_of_layers();
+    more = wave_any<S>(pair_of_layers());
   }
   return L.gmax(max(2 * k2, 2 * k1 - 1));
 }
@@ -453,15 +468,24 @@ __device__ __forceinline__ int neighbour_components(const Lanes<S>& L, typename 
     W V = go ? first_cell<S>(L, U) : (W)0;
     W pw = go ? passw : (W)0;
     k += go ? 1 : 0;
-    for (;;) {
+    // A group whose neighbours are all reached is finished for good: whatever its flood still
+    // adds while other groups go on changes nothing below.
+    bool more = true;
+    for (int n = 0; n < kShortTrips && more; ++n) {
       W V1 = L.grow(V, pw);
+      W Vn = L.grow(V1, pw);
+      bool ch = Vn != V1;  // a last layer that adds nothing means the flood is complete
+      V = Vn;
+      bool open = L.gany((U & ~V) != 0);
+      more = wave_any<S>(ch && open);
+    }
+    while (more) {
+      W V1 = L.grow(L.grow(L.grow(V, pw), pw), pw);
       W Vn = L.grow(V1, pw);
       bool ch = Vn != V1;
       V = Vn;
-      // a group whose neighbours are all reached is finished for good: whatever its flood still
-      // adds while other groups go on changes nothing below
       bool open = L.gany((U & ~V) != 0);
-      if (!wave_any<S>(ch && open)) break;
+      more = wave_any<S>(ch && open);
     }
     U &= ~V;
     left = count(U);
