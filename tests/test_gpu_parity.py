@@ -393,25 +393,28 @@ def _serpentine(n):
     return t
 
 
-def test_degenerate_and_extreme_levels():
+@pytest.mark.parametrize("n", [16, 32, 64])
+def test_degenerate_and_extreme_levels(n):
     """All-wall, all-empty, one-cell and one-row / one-column maps, and the longest possible
-    shortest path in a 64x64 buffer (a serpentine: 2078 edges, so the sweeps run ~1000 trips)."""
+    shortest path in an n x n buffer (a serpentine: 2078 edges for n = 64, so the sweeps and, once
+    the scanning agent cuts it, the region searches run hundreds of trips: the long-flood code of
+    every lane layout)."""
     dev = torch.device("cuda", 0)
     cases = []
-    n = 64
     cases.append(("all wall", np.ones((n, n), np.int8), (n, n)))
     cases.append(("all empty", np.zeros((n, n), np.int8), (n, n)))
     cases.append(("serpentine", _serpentine(n), (n, n)))
     one = np.full((n, n), -1, np.int8); one[0, 0] = 0
     cases.append(("single cell", one, (1, 1)))
-    row = np.full((n, n), -1, np.int8); row[0, :] = 0; row[0, 31] = 1
+    row = np.full((n, n), -1, np.int8); row[0, :] = 0; row[0, n // 2 - 1] = 1
     cases.append(("one row", row, (1, n)))
     col = np.full((n, n), -1, np.int8); col[:, 0] = 0
     cases.append(("one column", col, (n, 1)))
     checker = ((np.add.outer(np.arange(n), np.arange(n)) % 2) == 1).astype(np.int8)
     cases.append(("checkerboard", checker, (n, n)))
     B = len(cases)
-    cfg = wl.make_config(wl.BINARY, B, n, 63, min_size=1, autoreset=0, max_steps=10**6, pos_mode=wl.POS_SCAN)
+    cfg = wl.make_config(wl.BINARY, B, n, min(63, 2 * n - 1), min_size=1, autoreset=0, max_steps=10**6,
+                         pos_mode=wl.POS_SCAN)
     for lpw, rmode in ((0, wl.REGIONS_INCREMENTAL), (0, wl.REGIONS_RECOUNT)):
         gpu = binding.Pcgrl(dict(cfg, regions_mode=rmode, levels_per_wave=lpw), 0)
         cpu = oracle.Oracle(cfg)
@@ -425,12 +428,12 @@ def test_degenerate_and_extreme_levels():
         cpu.set_state(tiles, None, hw, pos)
         m = gpu.pcgrl_metrics().cpu().numpy()
         assert_same("metrics", m, cpu.metrics(), "degenerate levels")
-        assert list(m[:3, 0]) == [0, 1, 1] and list(m[:3, 1]) == [0, 126, 2078]
+        assert list(m[:3, 0]) == [0, 1, 1] and list(m[:3, 1]) == [0, 2 * (n - 1), n * n // 2 + n // 2 - 2]
         assert m[3, 0] == 1 and m[3, 1] == 0 and m[6, 0] == n * n // 2 and m[6, 1] == 0
         assert_same("obs", gpu.pcgrl_observe(), cpu.observe(), "degenerate levels")
         rew = torch.empty(B, dtype=torch.float32, device=dev)
         obs = gpu.new_obs()
-        for t in range(70):                      # flip the cell under the scanning agent
+        for t in range(n + 6):                   # flip the cell under the scanning agent
             st = cpu.get_state()
             cur = st["tiles"][np.arange(B), st["pos"][:, 0], st["pos"][:, 1]]
             a = (1 - cur).astype(np.int32)
@@ -440,6 +443,54 @@ def test_degenerate_and_extreme_levels():
             assert np.array_equal(rew.cpu().numpy(), r), f"flip {t}"
             assert_same("obs", obs, o, f"flip {t}")
         compare_state(gpu, cpu, "after flips")
+        gpu.close()
+
+
+@pytest.mark.parametrize("n", [16, 32, 64])
+def test_long_corridors_in_maze_and_dungeon(n):
+    """Player and door (and key, enemy) far apart along a serpentine corridor: path searches of
+    hundreds of layers, cut and re-joined by edits on the corridor."""
+    dev = torch.device("cuda", 0)
+    corridor = _serpentine(n)
+    ys, xs = np.nonzero(corridor == 0)
+    far_y = n - 2 if (n - 1) % 2 else n - 1           # the last open row
+    end_x = 0 if ((far_y // 2) % 2 == 1) else n - 1   # the corridor's far end in that row
+    path_len = n * n // 2 + n // 2 - 2
+    for pid in (wl.MAZE, wl.DUNGEON):
+        t = corridor.copy()
+        t[0, 0] = 2                                   # player at the start
+        if pid == wl.MAZE:
+            t[far_y, end_x] = 3                       # door at the far end
+        else:
+            t[far_y, end_x] = 4                       # door at the far end
+            t[(n // 2) & ~1, n // 2] = 3              # a key half way (an open row)
+            t[2, n // 2] = 5                          # an enemy near the start
+        B = 4
+        tiles = np.stack([t] * B)
+        hw = np.full((B, 2), n, np.int16)
+        # agents on the corridor: near the start, in the middle, near the end, and on the player
+        mid = len(ys) // 2
+        pos = np.array([[0, 3], [ys[mid], xs[mid]], [far_y, n // 2], [0, 0]], np.int16)
+        cfg = wl.make_config(pid, B, n, 5, min_size=1, autoreset=0, max_steps=10**6)
+        gpu, cpu = binding.Pcgrl(cfg, 0), oracle.Oracle(cfg)
+        gpu.pcgrl_reset(2)
+        cpu.reset(2)
+        gpu.pcgrl_set_state(torch.from_numpy(tiles).to(dev), None, torch.from_numpy(hw).to(dev),
+                            torch.from_numpy(pos).to(dev))
+        cpu.set_state(tiles, None, hw, pos)
+        m = gpu.pcgrl_metrics().cpu().numpy()
+        assert_same("metrics", m, cpu.metrics(), f"corridor {n}")
+        if pid == wl.MAZE:
+            assert m[0, 0] == 1 and m[0, 1] == path_len, m[0]
+        rew = torch.empty(B, dtype=torch.float32, device=dev)
+        K = wl.NUM_TILES[pid]
+        for step in range(24):                        # wall / re-open / other tiles under the agents
+            a = np.array([(1, 0, 1, 0)[step % 4], (1, 0)[step % 2], (step + 1) % K, (step * 3 + 1) % K], np.int32)
+            gpu.pcgrl_step(torch.from_numpy(a).to(dev), None, rew, None)
+            _, r, _ = cpu.step(a, want_obs=False)
+            assert_same("metrics", gpu.pcgrl_metrics(), cpu.metrics(), f"corridor {n} step {step}")
+            assert np.array_equal(rew.cpu().numpy(), r), f"corridor {n} step {step}"
+        compare_state(gpu, cpu, f"corridor {n}")
         gpu.close()
 
 
