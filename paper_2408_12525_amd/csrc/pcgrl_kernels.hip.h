@@ -677,8 +677,9 @@ __device__ __forceinline__ void obs_clear(uint32_t* lds, int lane, const ObsPlan
 }
 
 // Writes the observations of this wavefront's levels.  WIDE = window wider than 32; CLEARED = the
-// LDS words of the stream are zero already.
-template <int S, int PROBLEM, bool WIDE, bool CLEARED>
+// LDS words of the stream are zero already; LEAN = the caller is a wavefront that does nothing but
+// observations and can afford a copy of the channel code for every number of copies.
+template <int S, int PROBLEM, bool WIDE, bool CLEARED, bool LEAN>
 __device__ __forceinline__ void write_obs(const KArgs& a, const Lanes<S>& L, const Slot& sl,
                                           const ObsPlan& pl, uint32_t* lds,
                                           const typename RowWord<S>::T (&p)[Prob<PROBLEM>::P],
@@ -724,23 +725,59 @@ __device__ __forceinline__ void write_obs(const KArgs& a, const Lanes<S>& L, con
         if ((uint32_t)(t >> 32)) atomicOr(&lds[w0 + 1], (uint32_t)(t >> 32));
       }
     };
+    // One window row's channels, as far as they belong to this copy.  The copies of a level share
+    // the channels out in turn (channel c goes to copy c mod copies), so the low bits of a tile
+    // channel's code follow from the copy and the high bits from the trip: with the number of
+    // copies known at compile time, which planes a channel wants set costs one select per low bit,
+    // once, and nothing per channel.
+    const bool border = a.pad_mode == kPadBorder;
+    auto row_channels = [&](auto lc_tag, int off, BW in_row, BW pad_row, BW fz_row) {
+      constexpr int LC = decltype(lc_tag)::value, COPIES = 1 << LC;
+      BW low = in_row;
+#pragma unroll
+      for (int k = 0; k < LC && k < PR::P; ++k) low &= ((sl.copy >> k) & 1) ? wp[k] : (BW)~wp[k];
+#pragma unroll
+      for (int j = 0; j * COPIES < PR::K; ++j) {
+        BW bits = low;
+#pragma unroll
+        for (int k = LC; k < PR::P; ++k) bits &= ((j >> (k - LC)) & 1) ? wp[k] : (BW)~wp[k];
+        if (j * COPIES <= 1 && 1 < (j + 1) * COPIES)  // the wall channel doubles as padding
+          bits |= (!border && sl.copy == 1 - j * COPIES) ? pad_row : (BW)0;
+        const bool mine = (j + 1) * COPIES <= PR::K || j * COPIES + sl.copy < PR::K;
+        if (mine && bits != 0) emit(off + j * COPIES * cstride, bits);
+      }
+      if (border && sl.copy == (PR::K & (COPIES - 1)) && pad_row != 0)
+        emit(off + (PR::K - sl.copy) * cstride, pad_row);
+      if (a.obs_frozen_channel && sl.copy == (Cfz & (COPIES - 1)) && fz_row != 0)
+        emit(off + (Cfz - sl.copy) * cstride, fz_row);
+    };
+    auto row_channels_any = [&](int off, BW in_row, BW pad_row, BW fz_row) {
+      if (sl.copies_log2 == 0) {
+        row_channels(std::integral_constant<int, 0>{}, off, in_row, pad_row, fz_row);
+      } else if constexpr (LEAN && S <= 32) {
+        if (sl.copies_log2 == 1) row_channels(std::integral_constant<int, 1>{}, off, in_row, pad_row, fz_row);
+        if constexpr (S == 16) {
+          if (sl.copies_log2 == 2) row_channels(std::integral_constant<int, 2>{}, off, in_row, pad_row, fz_row);
+        }
+      } else {
+        // the general form: the channel's code is looked at bit by bit at run time
+        for (int c = sl.copy; c < C; c += sl.copies, off += sl.copies * cstride) {
+          BW bits = c < PR::K ? in_row : (BW)0;
+#pragma unroll
+          for (int k = 0; k < PR::P; ++k) bits &= ((c >> k) & 1) ? wp[k] : (BW)~wp[k];
+          bits |= c == padc ? pad_row : (BW)0;
+          if (c == Cfz) bits = fz_row;
+          if (bits != 0) emit(off, bits);
+        }
+      }
+    };
     if constexpr (S == 16) {
       // A 16-row buffer fills half of a typical window: every lane has rows above or below the
       // buffer to write, and those show nothing but padding.  Two passes (measured: 2-6 % ahead of
       // one loop over all rows and channels here, behind it for the larger buffers).
-      // (a) the lane's own row of the buffer, if the window shows it: every channel of this copy
+      // (a) the lane's own row of the buffer, if the window shows it
       const int i_own = L.y - y0;
-      if (i_own >= 0 && i_own < ow) {
-        int off = pl.lane_off + i_own * ow;
-        for (int c = sl.copy; c < C; c += sl.copies, off += sl.copies * cstride) {
-          BW bits = c < PR::K ? win_in : (BW)0;
-#pragma unroll
-          for (int k = 0; k < PR::P; ++k) bits &= ((c >> k) & 1) ? wp[k] : (BW)~wp[k];
-          bits |= c == padc ? out_win : (BW)0;
-          if (c == Cfz) bits = win_fz;
-          if (bits != 0) emit(off, bits);
-        }
-      }
+      if (i_own >= 0 && i_own < ow) row_channels_any(pl.lane_off + i_own * ow, win_in, out_win, win_fz);
       // (b) window rows above or below the buffer: only the padding channel shows them; the copy
       // that owns that channel writes them, the rows dealt out over its lanes
       if ((padc & (sl.copies - 1)) == sl.copy) {
@@ -751,17 +788,8 @@ __device__ __forceinline__ void write_obs(const KArgs& a, const Lanes<S>& L, con
     } else {
       for (int i = (L.y - y0) & (S - 1); i < ow; i += S) {
         const bool real = (y0 + i) == L.y;  // otherwise the row lies above or below the buffer
-        const BW in_real = real ? win_in : (BW)0;     // cells of this window row that lie in the map
-        const BW pad_bits = real ? out_win : owmask;  // cells of this window row that lie outside
-        int off = pl.lane_off + i * ow;
-        for (int c = sl.copy; c < C; c += sl.copies, off += sl.copies * cstride) {
-          BW bits = c < PR::K ? in_real : (BW)0;
-#pragma unroll
-          for (int k = 0; k < PR::P; ++k) bits &= ((c >> k) & 1) ? wp[k] : (BW)~wp[k];
-          bits |= c == padc ? pad_bits : (BW)0;
-          if (c == Cfz) bits = real ? win_fz : (BW)0;
-          if (bits != 0) emit(off, bits);
-        }
+        row_channels_any(pl.lane_off + i * ow, real ? win_in : (BW)0, real ? out_win : owmask,
+                         real ? win_fz : (BW)0);
       }
     }
   }
@@ -868,16 +896,16 @@ template <int S> struct WaveMap {
   }
 };
 
-template <int S, int PROBLEM, bool CLEARED = false>
+template <int S, int PROBLEM, bool CLEARED = false, bool LEAN = false>
 __device__ __forceinline__ void observe(const KArgs& a, const Lanes<S>& L, const WaveMap<S>& wm,
                                         const ObsPlan& pl,
                                         const typename RowWord<S>::T (&p)[Prob<PROBLEM>::P],
                                         typename RowWord<S>::T fz, typename RowWord<S>::T inside,
                                         int qy, int qx) {
   if (a.obs_w > 32)
-    write_obs<S, PROBLEM, true, CLEARED>(a, L, wm.sl, pl, wm.lds, p, fz, inside, qy, qx);
+    write_obs<S, PROBLEM, true, CLEARED, LEAN>(a, L, wm.sl, pl, wm.lds, p, fz, inside, qy, qx);
   else
-    write_obs<S, PROBLEM, false, CLEARED>(a, L, wm.sl, pl, wm.lds, p, fz, inside, qy, qx);
+    write_obs<S, PROBLEM, false, CLEARED, LEAN>(a, L, wm.sl, pl, wm.lds, p, fz, inside, qy, qx);
 }
 
 // Reset / refresh / observe: flags choose between generating a fresh episode 0 from the seed or
@@ -1060,7 +1088,7 @@ __device__ __forceinline__ void obs_wave_step(const KArgs& a, const Lanes<S>& L,
       qx = npx;
     }
   }
-  observe<S, PROBLEM, true>(a, L, wm, pl, p, fz, inside, qy, qx);
+  observe<S, PROBLEM, true, true>(a, L, wm, pl, p, fz, inside, qy, qx);
 }
 
 // The observation wavefront of a split rollout.  It needs nothing from the metrics wavefront: what
@@ -1150,7 +1178,8 @@ __device__ __forceinline__ void obs_wave_rollout(const KArgs& a, const Lanes<S>&
       }
     }
     uint8_t* obs = a.obs + (size_t)(step % a.obs_slots) * (size_t)a.B * (size_t)a.env_obs_bytes;
-    observe<S, PROBLEM>(a, L, wm, obs_plan(a, L.lane, wm.sl, obs, wm.env0, wm.nvalid), p, fz, inside, qy, qx);
+    observe<S, PROBLEM, false, true>(a, L, wm, obs_plan(a, L.lane, wm.sl, obs, wm.env0, wm.nvalid), p, fz, inside, qy,
+                                     qx);
     py = qy;
     px = qx;
     act = act_next;
