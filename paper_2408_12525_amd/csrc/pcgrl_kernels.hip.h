@@ -352,7 +352,9 @@ __device__ __forceinline__ int two_sweep_diameter(const Lanes<S>& L, typename Ro
 }
 
 // Distance from a source set to the nearest cell of a target set, -1 if none is reachable.
-// `reached` receives the target cells found in the layer of the first hit.
+// `reached` receives the target cells found in the layer of the first hit.  A trip looks for the
+// target in its last layer only; which layer of the trip met it first is worked out when that
+// happens, from the layers the trip has kept.
 template <int S>
 __device__ __forceinline__ int nearest(const Lanes<S>& L, typename RowWord<S>::T src,
                                        typename RowWord<S>::T tgt, typename RowWord<S>::T pass,
@@ -361,22 +363,33 @@ __device__ __forceinline__ int nearest(const Lanes<S>& L, typename RowWord<S>::T
   W V = src;
   int d = -1, it = 0;
   reached = 0;
-  for (;;) {  // two layers per trip
-    W V1 = L.grow(V, pass);
-    W V2 = L.grow(V1, pass);
-    uint64_t h1 = L.gbits(__builtin_amdgcn_ballot_w64((V1 & tgt) != 0));
-    uint64_t h2 = L.gbits(__builtin_amdgcn_ballot_w64((V2 & tgt) != 0));
-    bool ch = V2 != V1;  // a second layer that adds nothing means the flood is complete
-    V = V2;
-    if (d < 0 && h2 != 0) {  // the target set is hit in the first layer whenever h1 says so
-      d = h1 != 0 ? it + 1 : it + 2;
-      reached = (h1 != 0 ? V1 : V2) & tgt;
-      V = 0;
-      pass = 0;
-    }
-    it += 2;
-    if (!wave_any<S>(ch && d < 0)) break;
-  }
+  auto trip = [&](auto n_tag) {
+    constexpr int N = decltype(n_tag)::value;
+    W layer[N];
+#pragma unroll
+    for (int l = 0; l < N; ++l) layer[l] = L.grow(l == 0 ? V : layer[l - 1], pass);
+    const bool ch = layer[N - 1] != layer[N - 2];
+    V = layer[N - 1];
+    const bool hit = d < 0 && L.gany((V & tgt) != 0);
+    if (wave_any<S>(hit)) {
+      int first = N - 1;
+#pragma unroll
+      for (int l = N - 2; l >= 0; --l)
+        if (L.gany((layer[l] & tgt) != 0)) first = l;
+      if (hit) {
+        d = it + first + 1;
+        W at = layer[N - 1];
+#pragma unroll
+        for (int l = N - 2; l >= 0; --l) at = first == l ? layer[l] : at;
+        reached = at & tgt;
+      }
+    }  // (the level's flood may go on while others search: nothing reads it any more)
+    it += N;
+    return wave_any<S>(ch && d < 0);  // a last layer that adds nothing means the flood is complete
+  };
+  bool more = true;
+  for (int n = 0; n < kShortTrips && more; ++n) more = trip(std::integral_constant<int, 2>{});
+  while (more) more = trip(std::integral_constant<int, 4>{});
   return d;
 }
 
@@ -392,28 +405,38 @@ __device__ __forceinline__ void nearest_two(const Lanes<S>& L, typename RowWord<
   d_a = -1;
   d_b = -1;
   reached_a = 0;
-  for (;;) {  // two layers per trip
-    W V1 = L.grow(V, pass);
-    W V2 = L.grow(V1, pass);
-    uint64_t a1 = L.gbits(__builtin_amdgcn_ballot_w64((V1 & tgt_a) != 0));
-    uint64_t a2 = L.gbits(__builtin_amdgcn_ballot_w64((V2 & tgt_a) != 0));
-    uint64_t b1 = L.gbits(__builtin_amdgcn_ballot_w64((V1 & tgt_b) != 0));
-    uint64_t b2 = L.gbits(__builtin_amdgcn_ballot_w64((V2 & tgt_b) != 0));
-    bool ch = V2 != V1;
-    V = V2;
-    if (d_a < 0 && a2 != 0) {
-      d_a = a1 != 0 ? it + 1 : it + 2;
-      reached_a = (a1 != 0 ? V1 : V2) & tgt_a;
+  auto trip = [&](auto n_tag) {
+    constexpr int N = decltype(n_tag)::value;
+    W layer[N];
+#pragma unroll
+    for (int l = 0; l < N; ++l) layer[l] = L.grow(l == 0 ? V : layer[l - 1], pass);
+    const bool ch = layer[N - 1] != layer[N - 2];
+    V = layer[N - 1];
+    const bool hit_a = d_a < 0 && L.gany((V & tgt_a) != 0);
+    const bool hit_b = d_b < 0 && L.gany((V & tgt_b) != 0);
+    if (wave_any<S>(hit_a || hit_b)) {
+      int first_a = N - 1, first_b = N - 1;
+#pragma unroll
+      for (int l = N - 2; l >= 0; --l) {
+        if (L.gany((layer[l] & tgt_a) != 0)) first_a = l;
+        if (L.gany((layer[l] & tgt_b) != 0)) first_b = l;
+      }
+      if (hit_a) {
+        d_a = it + first_a + 1;
+        W at = layer[N - 1];
+#pragma unroll
+        for (int l = N - 2; l >= 0; --l) at = first_a == l ? layer[l] : at;
+        reached_a = at & tgt_a;
+      }
+      if (hit_b) d_b = it + first_b + 1;
     }
-    if (d_b < 0 && b2 != 0) d_b = b1 != 0 ? it + 1 : it + 2;
-    it += 2;
-    bool finished = d_a >= 0 && d_b >= 0;
-    if (finished) {
-      V = 0;
-      pass = 0;
-    }
-    if (!wave_any<S>(ch && !finished)) break;
-  }
+    it += N;
+    const bool finished = d_a >= 0 && d_b >= 0;
+    return wave_any<S>(ch && !finished);
+  };
+  bool more = true;
+  for (int n = 0; n < kShortTrips && more; ++n) more = trip(std::integral_constant<int, 2>{});
+  while (more) more = trip(std::integral_constant<int, 4>{});
 }
 
 // Number of 4-connected components of `pass`: single cells without walkable neighbour are counted
