@@ -67,7 +67,7 @@ extern "C" {
 #define PCGRL_OBS_STORE_STREAM 2 /* non-temporal stores */
 #define PCGRL_OBS_STORE_THROUGH 3 /* stores that write through the L2 as they are issued */
 
-#define PCGRL_SPLIT_AUTO 0 /* decide from the number of wavefronts the batch needs */
+#define PCGRL_SPLIT_AUTO 0 /* decide from the batch, the level size and the observation size */
 #define PCGRL_SPLIT_OFF 1  /* one wavefront per level group does the whole step */
 #define PCGRL_SPLIT_ON 2   /* pcgrl_step and pcgrl_rollout run a metrics wavefront and observation
                               wavefronts per group of levels (each holds the levels itself) */
