@@ -255,7 +255,7 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   // a step's observations are stored through the cache, 256-448 MB, where it costs 17 %), and of
   // 7 % for 32x32 levels with a 12 KB observation; a few percent either way elsewhere.
   const size_t obs_batch_bytes = E * (size_t)cfg->batch;
-  const bool obs_cached = obs_batch_bytes > ((size_t)256 << 20) && obs_batch_bytes <= ((size_t)448 << 20);
+  const bool obs_cached = obs_batch_bytes > ((size_t)256 << 20) && obs_batch_bytes <= ((size_t)448 << 20) && E >= 3072;
   ctx->split = ((ctx->S == 16 && (ctx->nwaves <= 2048 || (E >= 1536 && !obs_cached))) ||
                 (ctx->S == 32 && E >= 8192 && ctx->nwaves <= 8192)) ? 1 : 0;
   // A rollout split the same way (each wavefront keeps its own copy of the level for all the
@@ -340,14 +340,17 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   // write-back of whatever its stores left dirty, after the last wavefront: stores that write
   // through as they are issued overlap that traffic with the rest of the step (13 % of the step
   // at 20 MB of observations per step, a few percent at 200 MB); from about 256 MB per step on,
-  // ordinary stores, which the 256 MB last-level cache absorbs, are ahead, and far beyond the
-  // cache non-temporal stores.  A rollout launch has no such tail per step: non-temporal stores
+  // ordinary stores, which the 256 MB last-level cache absorbs, are ahead where one level's
+  // observation is large (4.8 KB: 65 against 81 us at 315 MB), non-temporal ones where it is small
+  // (1.9 KB: 79 against 86 us at 315 MB, 103 against 135 at 409 MB), and far beyond the cache
+  // non-temporal stores in any case.  A rollout launch has no such tail per step: non-temporal stores
   // for small batches (they keep the observation bytes out of the L2 that holds the action
   // stream), ordinary ones above, non-temporal ones far beyond the cache.
   {
     const size_t obs_step_bytes = (size_t)cfg->batch * E;
     const size_t MB = (size_t)1 << 20;
-    ctx->store_step = obs_step_bytes <= 256 * MB ? kStoreThrough : obs_step_bytes <= 448 * MB ? kStoreCached : kStoreStream;
+    ctx->store_step = obs_step_bytes <= 256 * MB ? kStoreThrough
+                      : (obs_step_bytes <= 448 * MB && E >= 3072) ? kStoreCached : kStoreStream;
     ctx->store_roll = (obs_step_bytes <= 32 * MB || obs_step_bytes > 448 * MB) ? kStoreStream : kStoreCached;
     const int forced = cfg->obs_store_mode == PCGRL_OBS_STORE_CACHED ? kStoreCached
                        : cfg->obs_store_mode == PCGRL_OBS_STORE_STREAM ? kStoreStream
