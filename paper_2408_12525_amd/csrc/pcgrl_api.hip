@@ -253,18 +253,20 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   // launch at the price of loading the level twice.  Measured: a gain of 10-25 % for 16x16 levels
   // up to 2048 wavefronts and of 2-13 % beyond (observations of 1.5 KB or more per level; not where
   // a step's observations are stored through the cache, 256-448 MB, where it costs 17 %), and of
-  // 7 % for 32x32 levels with a 12 KB observation; a few percent either way elsewhere.
+  // 7 % for 32x32 levels with a 12 KB observation; 4-16 % for 32x32 and 64x64 levels at batches
+  // up to 4096; a few percent either way elsewhere.
   const size_t obs_batch_bytes = E * (size_t)cfg->batch;
   const bool obs_cached = obs_batch_bytes > ((size_t)256 << 20) && obs_batch_bytes <= ((size_t)448 << 20) && E >= 3072;
   ctx->split = ((ctx->S == 16 && (ctx->nwaves <= 2048 || (E >= 1536 && !obs_cached))) ||
-                (ctx->S == 32 && E >= 8192 && ctx->nwaves <= 8192)) ? 1 : 0;
+                (ctx->S == 32 && E >= 8192 && ctx->nwaves <= 8192) ||
+                (ctx->S >= 32 && cfg->batch <= 4096)) ? 1 : 0;
   // A rollout split the same way (each wavefront keeps its own copy of the level for all the
   // steps): measured -35 % per step for 16x16 levels at batches of 64 and 1024, within a few
   // percent either way from 4096 on (100 steps per launch) except for observations of 4 KB or
-  // more at batches from 16 384 on (-4...-10 %); -6 % for 64x64 levels; within +-8 % either way
-  // for 32x32 levels.
+  // more at batches from 16 384 on (-4...-10 %); -6 % for 64x64 levels; for 32x32 levels -16...-43 %
+  // at batches up to 4096 and within +-10 % either way at 16 384.
   ctx->split_roll = ((ctx->S == 16 && (cfg->batch <= 2048 || (E >= 4096 && cfg->batch >= 16384))) ||
-                     (ctx->S == 64 && cfg->batch <= 8192)) ? 1 : 0;
+                     (ctx->S == 32 && cfg->batch <= 4096) || (ctx->S == 64 && cfg->batch <= 8192)) ? 1 : 0;
   if (cfg->split_step == PCGRL_SPLIT_OFF) ctx->split = ctx->split_roll = 0;
   if (cfg->split_step == PCGRL_SPLIT_ON) ctx->split = ctx->split_roll = 1;
   // Shape of the split step: one metrics wavefront carries as many levels as the explicit choice
