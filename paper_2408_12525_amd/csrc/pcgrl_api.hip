@@ -264,10 +264,12 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   // steps): measured -35 % per step for 16x16 levels at batches of 64 and 1024, within a few
   // percent either way from 4096 on (100 steps per launch) except for observations under 4 KB
   // up to a batch of 12 288 (-10...-30 %) and of 4 KB or more from 16 384 on (-4...-10 %); -6 % for 64x64 levels; for 32x32 levels -16...-43 %
-  // at batches up to 4096 and within +-10 % either way at 16 384.
+  // at batches up to 4096; beyond, -6...-9 % for the binary problem (two diameter sweeps a step) at
+  // every batch tried and +-2 % for the dungeon.
   ctx->split_roll = ((ctx->S == 16 && (cfg->batch <= 2048 || (E < 4096 && cfg->batch <= 12288) ||
                                        (E >= 4096 && cfg->batch >= 16384))) ||
-                     (ctx->S == 32 && cfg->batch <= 4096) || (ctx->S == 64 && cfg->batch <= 8192)) ? 1 : 0;
+                     (ctx->S == 32 && (cfg->batch <= 4096 || ctx->K == 2)) ||
+                     (ctx->S == 64 && cfg->batch <= 8192)) ? 1 : 0;
   if (cfg->split_step == PCGRL_SPLIT_OFF) ctx->split = ctx->split_roll = 0;
   if (cfg->split_step == PCGRL_SPLIT_ON) ctx->split = ctx->split_roll = 1;
   // Shape of the split step: one metrics wavefront carries as many levels as the explicit choice
