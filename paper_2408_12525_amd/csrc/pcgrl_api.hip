@@ -313,7 +313,9 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
       {&ctx->d_frozen, rows * ctx->word_bytes},
       {&ctx->d_env, (size_t)ctx->B_pad * sizeof(EnvRec)},
       {&ctx->d_metrics, (size_t)ctx->B_pad * kMaxMetrics * sizeof(int32_t)},
-      {&ctx->d_targets, (size_t)ctx->B_pad * kMaxMetrics * sizeof(uint32_t)},
+      // (one more row in front of the target ranges holds the reward weights: a step reads both
+      // through the one pointer it has at hand when it issues its loads)
+      {&ctx->d_targets, ((size_t)ctx->B_pad + 1) * kMaxMetrics * sizeof(uint32_t)},
       {&ctx->d_bad, sizeof(unsigned long long)},
   };
   for (auto& al : allocs) *al.p = nullptr;
@@ -332,8 +334,13 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   a.frozen = ctx->d_frozen;
   a.env = static_cast<EnvRec*>(ctx->d_env);
   a.metrics = static_cast<int32_t*>(ctx->d_metrics);
-  a.targets = static_cast<uint32_t*>(ctx->d_targets);
+  a.targets = static_cast<uint32_t*>(ctx->d_targets) + kMaxMetrics;
   a.bad_actions = static_cast<unsigned long long*>(ctx->d_bad);
+  if (hipMemcpy(ctx->d_targets, cfg->weights, kMaxMetrics * sizeof(float), hipMemcpyHostToDevice) != hipSuccess) {
+    for (auto& f : allocs) (void)hipFree(*f.p);
+    delete ctx;
+    return PCGRL_E_HIP;
+  }
   a.B = cfg->batch;
   a.plane_stride = (int32_t)rows;
   a.max_h = cfg->max_h;
@@ -377,7 +384,6 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   }
   for (int k = 0; k < 8; ++k) a.cdf[k] = cfg->init_cdf[k];
   for (int i = 0; i < kMaxMetrics; ++i) {
-    a.weights[i] = cfg->weights[i];
     a.target_lo[i] = cfg->target_lo[i];
     a.target_hi[i] = cfg->target_hi[i];
     a.ctrl_lo[i] = cfg->ctrl_lo[i];
@@ -515,7 +521,7 @@ int pcgrl_set_targets(pcgrl_ctx* ctx, const int32_t* targets, void* stream) {
   DeviceGuard guard(ctx->device);
   const int n = ctx->cfg.batch * ctx->M;
   hipLaunchKernelGGL(set_targets_kernel, dim3((n + 255) / 256), dim3(256), 0,
-                     static_cast<hipStream_t>(stream), targets, static_cast<uint32_t*>(ctx->d_targets),
+                     static_cast<hipStream_t>(stream), targets, static_cast<uint32_t*>(ctx->d_targets) + kMaxMetrics,
                      ctx->cfg.batch, ctx->M);
   return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
 }
@@ -525,7 +531,7 @@ int pcgrl_get_targets(pcgrl_ctx* ctx, int32_t* out, void* stream) {
   DeviceGuard guard(ctx->device);
   const int n = ctx->cfg.batch * ctx->M;
   hipLaunchKernelGGL(get_targets_kernel, dim3((n + 255) / 256), dim3(256), 0,
-                     static_cast<hipStream_t>(stream), static_cast<const uint32_t*>(ctx->d_targets),
+                     static_cast<hipStream_t>(stream), static_cast<const uint32_t*>(ctx->d_targets) + kMaxMetrics,
                      out, ctx->cfg.batch, ctx->M);
   return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
 }

@@ -51,7 +51,7 @@ struct KArgs {
   void* frozen;      // word [plane_stride]
   EnvRec* env;       // [B_pad]
   int32_t* metrics;  // [B_pad][16]
-  uint32_t* targets; // [B_pad][16], lo | hi << 16 (ranges are clamped to 0..65535)
+  uint32_t* targets; // [B_pad][16], lo | hi << 16 (ranges are clamped to 0..65535); the 16 words in front of it: the reward weights (float)
   const int32_t* actions;
   int32_t B, plane_stride;
   int32_t envs_per_wave_log2;  // bits 0-7: log2 of the distinct levels per wavefront (at most 64 / S);
@@ -73,7 +73,6 @@ struct KArgs {
   int32_t obs_slots;      // rollout kernel: step t writes observation slot t % obs_slots
   int32_t obs_lds_words;  // split step: LDS words of one observation wavefront's staging area
   uint32_t cdf[8];
-  float weights[kMaxMetrics];
   int32_t target_lo[kMaxMetrics], target_hi[kMaxMetrics];
   int32_t pinpoint_tile[8];
   uint32_t ctrl_mask;
@@ -864,20 +863,6 @@ __device__ __forceinline__ void write_obs(const KArgs& a, const Lanes<S>& L, con
 // ------------------------------------------------------------------ kernels
 
 template <int S, int PROBLEM>
-__device__ __forceinline__ void load_metrics(const int32_t* src, int (&m)[Prob<PROBLEM>::M]) {
-  constexpr int M = Prob<PROBLEM>::M;
-  const int4* v = reinterpret_cast<const int4*>(src);
-#pragma unroll
-  for (int q = 0; q < (M + 3) / 4; ++q) {
-    int4 t = v[q];
-    if (4 * q + 0 < M) m[4 * q + 0] = t.x;
-    if (4 * q + 1 < M) m[4 * q + 1] = t.y;
-    if (4 * q + 2 < M) m[4 * q + 2] = t.z;
-    if (4 * q + 3 < M) m[4 * q + 3] = t.w;
-  }
-}
-
-template <int S, int PROBLEM>
 __device__ __forceinline__ void store_metrics(int32_t* dst, const int (&m)[Prob<PROBLEM>::M]) {
   constexpr int M = Prob<PROBLEM>::M;
   int4* v = reinterpret_cast<int4*>(dst);
@@ -1262,21 +1247,17 @@ __global__ __launch_bounds__(MODE == kModeSplit || MODE == kModeRolloutSplit ? 3
   const uint4* erp = reinterpret_cast<const uint4*>(a.env + wm.envl);
   const uint4 er0 = erp[0], er1 = erp[1];  // unpacked below, after all loads are under way
   int act = a.actions[wm.envl];  // (lanes without a level of their own read a neighbour's and ignore it)
-  int mo[PR::M];
-  load_metrics<S, PROBLEM>(a.metrics + (size_t)wm.envl * kMaxMetrics, mo);
-  constexpr int kTg = (PR::M + 3) / 4 * 4;
-  uint32_t tg[kTg];  // packed target ranges
-  {
-    const uint4* tv = reinterpret_cast<const uint4*>(a.targets + (size_t)wm.envl * kMaxMetrics);
-#pragma unroll
-    for (int q = 0; q < kTg / 4; ++q) {
-      uint4 t = tv[q];
-      tg[4 * q + 0] = t.x;
-      tg[4 * q + 1] = t.y;
-      tg[4 * q + 2] = t.z;
-      tg[4 * q + 3] = t.w;
-    }
-  }
+  // The metric vector, its target ranges and the reward weights are kept one entry per lane
+  // (lane y of a group holds entry y): what an edit does to them - one tile count up, one down, up
+  // to three flood results replaced, one loss difference per metric - is then a handful of
+  // instructions for the whole vector instead of a handful per metric.  Only the region count is
+  // also needed by every lane (the incremental update starts from it).
+  const int yi = L.y & (kMaxMetrics - 1);
+  const size_t mrow = (size_t)wm.envl * kMaxMetrics;
+  int m_l = a.metrics[mrow + yi];
+  uint32_t tg_l = a.targets[mrow + yi];
+  int regions_now = a.metrics[mrow];
+  const float w_l = __uint_as_float((a.targets - kMaxMetrics)[yi]);  // (the row in front of the ranges)
   // every load above is issued before anything below waits for one of them
   __builtin_amdgcn_sched_barrier(0);
   // the observation wavefront has issued its loads of the old state before this wavefront goes
@@ -1381,23 +1362,23 @@ __global__ __launch_bounds__(MODE == kModeSplit || MODE == kModeRolloutSplit ? 3
     }
 
     // ---- metrics, only where the edit modified the map (Methods / Task)
-    int mn[PR::M];
-#pragma unroll
-    for (int i = 0; i < PR::M; ++i) mn[i] = mo[i];
-    float reward = 0.0f;
+    int mn_l = m_l;               // this lane's entry of the new metric vector
+    int regions_new = regions_now;
+    float reward = 0.0f;          // (ends up in lane M-1 of the group)
     if (wave_any<S>(changed)) {
       const W in = changed ? inside : (W)0;  // unchanged levels look empty: their loops end at once
       const W wall = channel_row<PROBLEM, W>(p, in, 1);
       const W pass = in & ~wall;
       // tile counts: one cell moved from one tile type to another
-#pragma unroll
-      for (int k = 0; k < PR::K; ++k)
-        mn[PR::CNT + k] += (changed && act == k ? 1 : 0) - (changed && old_code == k ? 1 : 0);
+      {
+        const int k = yi - PR::CNT;  // the tile type whose count this lane keeps, if any
+        mn_l += (changed && act == k ? 1 : 0) - (changed && old_code == k ? 1 : 0);
+      }
       const bool was_pass = old_code != 1, now_pass = act != 1;
       // regions
       if (a.regions_mode == kRegionsRecount) {
         int rc = regions_full<S>(L, pass);
-        if (changed) mn[0] = rc;
+        if (changed) regions_new = rc;
       } else {
         const bool flip = changed && was_pass != now_pass;
         if (wave_any<S>(flip)) {
@@ -1405,17 +1386,18 @@ __global__ __launch_bounds__(MODE == kModeSplit || MODE == kModeRolloutSplit ? 3
           W passw = flip ? (pass & ~cell) : (W)0;
           W nbr = (L.dilate(cell) & ~cell) & passw;
           int k = neighbour_components<S>(L, nbr, passw);
-          if (flip) mn[0] = mo[0] + (now_pass ? 1 - k : k - 1);
+          if (flip) regions_new = regions_now + (now_pass ? 1 - k : k - 1);
         }
       }
+      if (yi == 0) mn_l = regions_new;
       // paths
       if constexpr (PROBLEM == kBinary) {
         int dm = two_sweep_diameter<S>(L, pass);
-        if (changed) mn[1] = dm;
+        if (changed && yi == 1) mn_l = dm;
       } else if constexpr (PROBLEM == kMaze) {
         W r;
         int dd = nearest<S>(L, channel_row<PROBLEM, W>(p, in, 2), channel_row<PROBLEM, W>(p, in, 3), pass, r);
-        if (changed) mn[1] = dd < 0 ? 0 : dd;
+        if (changed && yi == 1) mn_l = dd < 0 ? 0 : dd;
       } else {
         // swapping empty and chest changes neither the graph nor any source or target set
         const bool plain = (old_code == 0 || old_code == 6) && (act == 0 || act == 6);
@@ -1428,20 +1410,23 @@ __global__ __launch_bounds__(MODE == kModeSplit || MODE == kModeRolloutSplit ? 3
           nearest_two<S>(L, channel_row<PROBLEM, W>(p, inn, 2), channel_row<PROBLEM, W>(p, inn, 3),
                          channel_row<PROBLEM, W>(p, inn, 5), passn, d1, k1, de);
           int d2 = nearest<S>(L, k1, channel_row<PROBLEM, W>(p, inn, 4), passn, r);
-          if (need) {
-            mn[1] = (d1 >= 0 && d2 >= 0) ? d1 + d2 : 0;
-            mn[2] = de < 0 ? 0 : de;
-          }
+          if (need && yi == 1) mn_l = (d1 >= 0 && d2 >= 0) ? d1 + d2 : 0;
+          if (need && yi == 2) mn_l = de < 0 ? 0 : de;
         }
       }
-      // reward = sum over metrics, in index order, of weight * (old loss - new loss)
-      if (changed) {
+      // reward = sum over metrics, in index order, of weight * (old loss - new loss): every lane
+      // its own term; then M-1 times every lane adds its term to what the lane before it holds, so
+      // that lane k ends with ((t[k-M+1] + ...) + t[k-1]) + t[k], terms before the first lane
+      // counting as zero: in lane M-1 that is the sum in index order
+      {
+        const int lo = (int)(tg_l & 0xffffu), hi = (int)(tg_l >> 16);
+        const int dl = loss(m_l, lo, hi) - loss(mn_l, lo, hi);
+        const float term = __fmul_rn(w_l, (float)dl);
+        float acc = __fadd_rn(0.0f, term);
 #pragma unroll
-        for (int i = 0; i < PR::M; ++i) {
-          const int lo = (int)(tg[i] & 0xffffu), hi = (int)(tg[i] >> 16);
-          int dl = loss(mo[i], lo, hi) - loss(mn[i], lo, hi);
-          reward = __fadd_rn(reward, __fmul_rn(a.weights[i], (float)dl));
-        }
+        for (int j = 1; j < PR::M; ++j)
+          acc = __fadd_rn(__int_as_float((int)dpp_zero_fill<kRowShr1>((uint32_t)__float_as_int(acc))), term);
+        if (changed) reward = acc;
       }
     }
     // ---- auto-reset: fresh seeded episode for the finished levels; the others keep their registers
@@ -1471,13 +1456,13 @@ __global__ __launch_bounds__(MODE == kModeSplit || MODE == kModeRolloutSplit ? 3
         fz_dirty = true;
         metrics_dirty = true;
         if (ra.ctrl_mask != 0) {
-#pragma unroll
-          for (int i = 0; i < PR::M; ++i)
-            if ((ra.ctrl_mask >> i) & 1u) tg[i] = control_target(ra, nkey, i);
+          if ((ra.ctrl_mask >> yi) & 1u) tg_l = control_target(ra, nkey, yi);
           targets_dirty = true;
         }
 #pragma unroll
-        for (int i = 0; i < PR::M; ++i) mn[i] = nm[i];
+        for (int i = 0; i < PR::M; ++i)
+          if (yi == i) mn_l = nm[i];
+        regions_new = nm[0];
         inside = ninside;
         h = nh;
         w = nw;
@@ -1499,8 +1484,10 @@ __global__ __launch_bounds__(MODE == kModeSplit || MODE == kModeRolloutSplit ? 3
         asm volatile("" : "+v"(next_cell_frozen));
       }
     }
-    if (wm.primary && L.y == 0) {
+    if (wm.primary && L.y == PR::M - 1) {
       if (a.reward) a.reward[(size_t)step * a.B + wm.env] = reward;
+    }
+    if (wm.primary && L.y == 0) {
       if (a.done) a.done[(size_t)step * a.B + wm.env] = done ? 1 : 0;
     }
     if constexpr (!SPLIT) {
@@ -1510,8 +1497,8 @@ __global__ __launch_bounds__(MODE == kModeSplit || MODE == kModeRolloutSplit ? 3
     // ---- the new state becomes the current one
     py = qy;
     px = qx;
-#pragma unroll
-    for (int i = 0; i < PR::M; ++i) mo[i] = mn[i];
+    m_l = mn_l;
+    regions_now = regions_new;
     act = act_next;
   }
 
@@ -1533,12 +1520,10 @@ __global__ __launch_bounds__(MODE == kModeSplit || MODE == kModeRolloutSplit ? 3
     er.px = (uint8_t)px;
     er.cell_frozen = ROLL ? (uint32_t)((next_fz_row >> px) & 1) : next_cell_frozen;
     a.env[wm.env] = er;
-    if (metrics_dirty) store_metrics<S, PROBLEM>(a.metrics + (size_t)wm.env * kMaxMetrics, mo);
-    if (targets_dirty) {
-      uint4* tv = reinterpret_cast<uint4*>(a.targets + (size_t)wm.env * kMaxMetrics);
-#pragma unroll
-      for (int q = 0; q < kTg / 4; ++q) tv[q] = make_uint4(tg[4 * q], tg[4 * q + 1], tg[4 * q + 2], tg[4 * q + 3]);
-    }
+  }
+  if (wm.primary && L.y < PR::M) {
+    if (metrics_dirty) a.metrics[(size_t)wm.env * kMaxMetrics + L.y] = m_l;
+    if (targets_dirty) a.targets[(size_t)wm.env * kMaxMetrics + L.y] = tg_l;
   }
   if constexpr (SPLIT) __builtin_amdgcn_endpgm();  // see the observation wavefront's exit above
 }

@@ -28,8 +28,9 @@ def run_parity(cfg, steps, seed=1, aseed=2, bad_fraction=0.0, check_every=1, sta
                env_slice=None, targets=None, label=""):
     """Steps both implementations `steps` times.  Observations, rewards, done flags and metrics
     are compared every `check_every` steps (all envs, or `env_slice` of them); the plain-layout
-    state every `state_every` steps and at the end.  Rewards must agree to 1e-6 absolute (they
-    are bit-equal when the weights are small integers)."""
+    state every `state_every` steps and at the end.  Rewards must be equal: both sides add the
+    same float32 products in the same order, without fused multiply-adds (the bar the task sets is
+    1e-6 absolute)."""
     print(f"[parity] {label} cfg={ {k: cfg[k] for k in ('problem','batch','max_h','max_w','min_h','obs_w','pad_mode','pos_mode','n_frozen','max_steps','regions_mode')} } steps={steps}", flush=True)
     dev = torch.device("cuda", 0)
     gpu = binding.Pcgrl(cfg, 0)
@@ -58,7 +59,7 @@ def run_parity(cfg, steps, seed=1, aseed=2, bad_fraction=0.0, check_every=1, sta
             assert_same("done", done[sl], d[sl], ctx)
             assert_same("metrics", gpu.pcgrl_metrics()[sl], cpu.metrics()[sl], ctx)
             g = rew.cpu().numpy()
-            bad = np.flatnonzero(~(np.abs(g[sl] - r[sl]) <= 1e-6))
+            bad = np.flatnonzero(~(g[sl] == r[sl]))
             assert len(bad) == 0, (f"reward differs {ctx} in {len(bad)} envs; first env {bad[0]}: "
                                    f"gpu={g[sl][bad[0]]} oracle={r[sl][bad[0]]}")
             assert_same("obs", obs[sl], expected_obs(cfg, o)[sl], ctx)

@@ -146,7 +146,7 @@ def test_pinpoint_channel_after_set_state():
 
 
 def test_control_targets_and_fractional_weights():
-    # per-env target ranges and non-integer weights: rewards must still agree to 1e-6
+    # per-env target ranges and non-integer weights (products that round): rewards must still be equal
     cfg = wl.make_config(wl.DUNGEON, 32, 16, 9, max_steps=10**6, autoreset=0,
                          weights=[0.37, 1.13, 0.71, 0.0, 0.05, 2.9, 3.3, 1.7, 0.9, 0.11])
     rng = np.random.default_rng(0)
