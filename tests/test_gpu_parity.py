@@ -494,6 +494,61 @@ def test_long_corridors_in_maze_and_dungeon(n):
         gpu.close()
 
 
+def _rollout_against_oracle(cfg, T, slots, seed):
+    dev = torch.device("cuda", 0)
+    B = cfg["batch"]
+    acts_np = wl.random_actions(cfg, seed, T, bad_fraction=0.02)
+    roll, cpu = binding.Pcgrl(cfg, 0), oracle.Oracle(cfg)
+    roll.pcgrl_reset(seed)
+    cpu.reset(seed)
+    obs = torch.zeros((slots,) + roll.obs_shape, dtype=torch.uint8, device=dev)
+    rew = torch.empty((T, B), dtype=torch.float32, device=dev)
+    done = torch.empty((T, B), dtype=torch.uint8, device=dev)
+    roll.pcgrl_rollout(torch.from_numpy(acts_np).to(dev), obs, rew, done)
+    want = {}
+    for t in range(T):
+        o, r, d = cpu.step(acts_np[t])
+        want[t % slots] = expected_obs(cfg, o)
+        assert np.array_equal(rew[t].cpu().numpy(), r), f"reward step {t}"
+        assert np.array_equal(done[t].cpu().numpy(), d), f"done step {t}"
+    for k, o in want.items():
+        assert_same("obs", obs[k], o, f"slot {k}")
+    assert_same("metrics", roll.pcgrl_metrics(), cpu.metrics(), "after rollout")
+    compare_state(roll, cpu, "after rollout")
+    roll.close()
+
+
+def test_random_configurations_and_launch_shapes():
+    """Seeded random draws over everything a configuration has - problem, buffer and minimum size,
+    window, padding, position mode, pinpoints, step and change budgets, auto-reset, real-valued
+    weights, a controlled target, output format - and over every tuning knob (levels per
+    wavefront, split, store mode, observation wavefronts), at batches on both sides of every
+    automatic launch rule: single steps and a rollout against the oracle, rewards equal."""
+    rng = np.random.default_rng(5)
+    for n in range(48):
+        problem = int(rng.integers(0, 3))
+        size = int(rng.choice([5, 9, 16, 16, 23, 32, 32, 47, 64]))
+        ow = int(rng.choice([1, 3, 5, 8, 15, 22, 31, 33, 47, 63]))
+        batch = int(rng.choice([1, 3, 37, 64, 130, 513, 1000, 2049, 4100, 9001]))
+        if size > 32:
+            batch = min(batch, 2049)
+        ms = int(rng.integers(1, size + 1)) if rng.random() < 0.6 else None
+        nf = min(int(rng.choice([0, 0, 1, 3])), (ms if ms is not None else size) ** 2)
+        cfg = wl.make_config(
+            problem, batch, size, ow, min_size=ms, pad_mode=int(rng.integers(0, 2)),
+            pos_mode=int(rng.integers(0, 2)), n_frozen=nf, max_steps=int(rng.choice([7, 19, 1000])),
+            max_changes=int(rng.choice([0, 0, 5])), autoreset=int(rng.integers(0, 2)),
+            levels_per_wave=int(rng.choice([0, 0, 1, 2, 4])), split_step=int(rng.choice([0, 0, 1, 2])),
+            obs_store_mode=int(rng.choice([0, 0, 1, 2, 3])), obs_format=int(rng.choice([0, 0, 1])),
+            obs_frozen_channel=int(rng.integers(0, 2)), split_obs_levels=int(rng.choice([0, 0, 1, 2])),
+            weights=[float(v) for v in rng.uniform(-2, 4, size=16).astype(np.float32)] if rng.random() < 0.5 else None,
+            ctrl={1: (3, 40)} if rng.random() < 0.3 else None)
+        steps = 20 if batch * size * size < 3e6 else 8
+        run_parity(cfg, steps, seed=int(rng.integers(1, 1000)), aseed=int(rng.integers(1, 1000)),
+                   bad_fraction=0.02, state_every=steps, label=f"random configuration {n}")
+        _rollout_against_oracle(cfg, steps, int(rng.choice([1, 2, steps])), int(rng.integers(1, 1000)))
+
+
 def test_small_buffers_and_every_window_size():
     """Buffers smaller than a lane group (5x3, 1x1) and every window size 1..63 on a 16x16 maze."""
     run_parity(wl.make_config(wl.MAZE, 9, 5, 7, max_w=3, min_size=1, min_w=1, max_steps=11), 40, label="5x3 buffer")
