@@ -161,7 +161,8 @@ int pcgrl_reset(pcgrl_ctx* ctx, uint64_t seed, uint8_t* obs, void* stream);
  *            NEW cell; C = K, plus 1 under PCGRL_PAD_BORDER, plus 1 with obs_frozen_channel
  *            (bit-packed under PCGRL_OBS_PACKED).  May be NULL.
  *   reward : device, float32 [batch]: sum over metrics, in index order, of
- *            weight * (loss before - loss after); exactly 0 when the edit was a no-op.
+ *            weight * (loss before - loss after), each product and each partial sum rounded to
+ *            float32 (no fused multiply-add); exactly 0 when the edit was a no-op.
  *   done   : device, uint8 [batch].
  * reward and done may be NULL.
  * The call only enqueues one kernel launch, so it may be captured into a HIP graph; a captured
