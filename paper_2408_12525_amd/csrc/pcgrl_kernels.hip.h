@@ -1329,7 +1329,7 @@ __global__ __launch_bounds__(MODE == kModeSplit || MODE == kModeRolloutSplit ? 3
     else is_frozen = er.cell_frozen != 0;
     const bool in_range = act >= 0 && act < PR::K;
     const bool changed = valid && in_range && !is_frozen && act != old_code;
-    {
+    if (__builtin_amdgcn_ballot_w64((uint32_t)act >= (uint32_t)PR::K) != 0) {  // rare: count them
       const uint64_t bad = __builtin_amdgcn_ballot_w64(wm.primary && !in_range && L.y == 0);
       if (bad != 0 && L.lane == 0) atomicAdd(a.bad_actions, (unsigned long long)__popcll(bad));
     }
