@@ -367,15 +367,15 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   // ordinary stores, which the 256 MB last-level cache absorbs, are ahead where one level's
   // observation is large (4.8 KB: 65 against 81 us at 315 MB), non-temporal ones where it is small
   // (1.9 KB: 79 against 86 us at 315 MB, 103 against 135 at 409 MB), and far beyond the cache
-  // non-temporal stores in any case.  A rollout launch has no such tail per step: non-temporal stores
-  // for small batches (they keep the observation bytes out of the L2 that holds the action
-  // stream), ordinary ones above, non-temporal ones far beyond the cache.
+  // non-temporal stores in any case.  A rollout launch has no such tail per step: ordinary stores
+  // (equal to or up to 6 % ahead of the others at every batch tried), non-temporal ones far
+  // beyond the cache.
   {
     const size_t obs_step_bytes = (size_t)cfg->batch * E;
     const size_t MB = (size_t)1 << 20;
     ctx->store_step = obs_step_bytes <= 256 * MB ? kStoreThrough
                       : (obs_step_bytes <= 448 * MB && E >= 3072) ? kStoreCached : kStoreStream;
-    ctx->store_roll = (obs_step_bytes <= 32 * MB || obs_step_bytes > 448 * MB) ? kStoreStream : kStoreCached;
+    ctx->store_roll = obs_step_bytes > 448 * MB ? kStoreStream : kStoreCached;
     const int forced = cfg->obs_store_mode == PCGRL_OBS_STORE_CACHED ? kStoreCached
                        : cfg->obs_store_mode == PCGRL_OBS_STORE_STREAM ? kStoreStream
                        : cfg->obs_store_mode == PCGRL_OBS_STORE_THROUGH ? kStoreThrough : -1;
