@@ -216,13 +216,17 @@ def main():
                      "kernel": "step_kernel", "avg_launch_us": launch_s * 1e6},
     }
     # The same K steps driven through pcgrl_rollout: T steps per launch, levels resident in
-    # registers in between, every step still writes its observation (into one slot, as the loop
-    # above does), reward and done flag.  Reported beside the headline, never instead of it.
+    # registers in between, every step still writes its observation, reward and done flag.  The
+    # observations go into a slot per step (what a learner that keeps the whole rollout needs;
+    # fewer slots only where T of them would exceed 16 GiB), so that every byte written has to
+    # reach HBM: one slot rewritten T times would largely be absorbed by the caches.  Reported
+    # beside the headline, never instead of it.
     if not args.no_rollout:
         T = min(chunk, 100)
         launches = max(1, K // T)
         racts = acts[:T].contiguous()
-        robs = obs.unsqueeze(0)
+        slots = max(1, min(T, (16 << 30) // max(1, obs.numel())))
+        robs = torch.empty((slots,) + tuple(obs.shape), dtype=torch.uint8, device=dev)
         rrew = torch.empty((T, B), dtype=torch.float32, device=dev)
         rdone = torch.empty((T, B), dtype=torch.uint8, device=dev)
         env.pcgrl_reset(seed, obs)
@@ -241,7 +245,7 @@ def main():
         rlaunch_s = r0.elapsed_time(r1) * 1e-3 / launches
         out["rollout"] = {
             "value": B * T * launches / rwall, "unit": "env-steps/s", "steps_per_launch": T,
-            "launches": launches, "us_per_step": rwall / (T * launches) * 1e6,
+            "launches": launches, "obs_slots": slots, "us_per_step": rwall / (T * launches) * 1e6,
             "algorithmic_bytes_per_env_step": rbytes,
             "roofline": {"bound": "hbm", "achieved": rbytes * B * T / rlaunch_s / 1e9,
                          "peak": HBM_PEAK_GBS, "unit": "GB/s",

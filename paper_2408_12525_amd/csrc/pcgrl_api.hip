@@ -262,12 +262,16 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
                 (ctx->S >= 32 && cfg->batch <= 4096)) ? 1 : 0;
   // A rollout split the same way (each wavefront keeps its own copy of the level for all the
   // steps): measured -35 % per step for 16x16 levels at batches of 64 and 1024, within a few
-  // percent either way from 4096 on (100 steps per launch) except for observations under 4 KB
-  // up to a batch of 12 288 (-10...-30 %) and of 4 KB or more from 16 384 on (-4...-10 %); -6 % for 64x64 levels; for 32x32 levels -16...-43 %
+  // percent either way from 4096 on (100 steps per launch) except: observations under 4 KB up to a
+  // batch of 12 288 (-10...-30 %), and at every batch tried when they are 1.5 KB or more (binary16:
+  // -5...-9 % from 16 384 to 131 072); observations of 4 KB or more up to 4096 (maze16 -20 %) and
+  // from 16 384 on (-2...-3 %), but not between (8192: +6 %); -6 % for 64x64 levels; for 32x32 levels -16...-43 %
   // at batches up to 4096; beyond, -6...-9 % for the binary problem (two diameter sweeps a step) at
   // every batch tried and +-2 % for the dungeon.
-  ctx->split_roll = ((ctx->S == 16 && (cfg->batch <= 2048 || (E < 4096 && cfg->batch <= 12288) ||
-                                       (E >= 4096 && cfg->batch >= 16384))) ||
+  const bool obs_heavy = E >= 4096;
+  ctx->split_roll = ((ctx->S == 16 && (cfg->batch <= 2048 ||
+                                       (!obs_heavy && (cfg->batch <= 12288 || E >= 1536)) ||
+                                       (obs_heavy && (cfg->batch <= 4096 || cfg->batch >= 16384)))) ||
                      (ctx->S == 32 && (cfg->batch <= 4096 || ctx->K == 2)) ||
                      (ctx->S == 64 && cfg->batch <= 8192)) ? 1 : 0;
   if (cfg->split_step == PCGRL_SPLIT_OFF) ctx->split = ctx->split_roll = 0;
@@ -300,7 +304,12 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   // it packs as many levels into a wavefront as leave about a thousand workgroups (measured).
   ctx->roll_m = ctx->G;
   while (ctx->roll_m > 1 && (cfg->batch + ctx->roll_m - 1) / ctx->roll_m < 1024) ctx->roll_m /= 2;
-  ctx->roll_o = (ctx->roll_m == 4 && cfg->batch / ctx->roll_m >= 4096) ? 2 : ctx->roll_m;
+  // Observation wavefronts of a split rollout: one for all the levels of the metrics wavefront
+  // where the observation is small, two (or one per level) where it is the larger half of the
+  // work (measured on 16x16 levels: maze16 at 4096, 2.8 against 3.2 us per step; binary16 at
+  // 16 384, 6.4 against 7.6 the other way round).
+  ctx->roll_o = ctx->roll_m;
+  if (ctx->S == 16 && obs_heavy && ctx->roll_m >= 2) ctx->roll_o = ctx->roll_m / 2;
   if (cfg->levels_per_wave > 0) ctx->roll_m = ctx->roll_o = ctx->split_m;
   if (cfg->split_obs_levels > 0) ctx->roll_o = ctx->split_o < ctx->roll_m ? ctx->split_o : ctx->roll_m;
   ctx->roll_groups = (cfg->batch + ctx->roll_m - 1) / ctx->roll_m;
@@ -367,15 +376,18 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   // ordinary stores, which the 256 MB last-level cache absorbs, are ahead where one level's
   // observation is large (4.8 KB: 65 against 81 us at 315 MB), non-temporal ones where it is small
   // (1.9 KB: 79 against 86 us at 315 MB, 103 against 135 at 409 MB), and far beyond the cache
-  // non-temporal stores in any case.  A rollout launch has no such tail per step: ordinary stores
-  // (equal to or up to 6 % ahead of the others at every batch tried), non-temporal ones far
-  // beyond the cache.
+  // non-temporal stores in any case.  A rollout launch has no such tail per step, and what counts
+  // is the whole ring of observation slots it writes: while that fits the last-level cache, ordinary
+  // stores (equal to or up to 6 % ahead of the others at every batch tried); beyond it, ordinary
+  // stores for large observations (maze16, a slot per step: 4.4 against 4.9 us per step; maze64
+  // 11.0 against 11.8) and non-temporal ones for small ones (binary16 3.0 against 3.2, dungeon32
+  // 9.5 against 10.4).  Decided per pcgrl_rollout call, which knows the number of slots.
   {
     const size_t obs_step_bytes = (size_t)cfg->batch * E;
     const size_t MB = (size_t)1 << 20;
     ctx->store_step = obs_step_bytes <= 256 * MB ? kStoreThrough
                       : (obs_step_bytes <= 448 * MB && E >= 3072) ? kStoreCached : kStoreStream;
-    ctx->store_roll = obs_step_bytes > 448 * MB ? kStoreStream : kStoreCached;
+    ctx->store_roll = -1;  // by ring size, see pcgrl_rollout
     const int forced = cfg->obs_store_mode == PCGRL_OBS_STORE_CACHED ? kStoreCached
                        : cfg->obs_store_mode == PCGRL_OBS_STORE_STREAM ? kStoreStream
                        : cfg->obs_store_mode == PCGRL_OBS_STORE_THROUGH ? kStoreThrough : -1;
@@ -452,7 +464,12 @@ int pcgrl_rollout(pcgrl_ctx* ctx, const int32_t* actions, int32_t n_steps, uint8
   a.done = done;
   a.rollout_steps = n_steps;
   a.obs_slots = obs ? obs_slots : 1;
-  a.stream_obs = ctx->store_roll;
+  if (ctx->store_roll >= 0) {
+    a.stream_obs = ctx->store_roll;
+  } else {
+    const size_t ring = (size_t)a.obs_slots * (size_t)ctx->cfg.batch * ctx->obs_bytes;
+    a.stream_obs = (ring <= ((size_t)448 << 20) || ctx->obs_bytes >= 3072) ? kStoreCached : kStoreStream;
+  }
   if (obs && ctx->split_roll) {
     auto lg2 = [](int v) { return v == 4 ? 2 : v == 2 ? 1 : 0; };
     a.envs_per_wave_log2 = lg2(ctx->roll_m) | (lg2(ctx->roll_o) << 8);
