@@ -47,7 +47,7 @@ extern "C" {
 #define PCGRL_E_CONFIG (-2)   /* a configuration field is out of range */
 #define PCGRL_E_HIP (-3)      /* a HIP runtime call failed */
 #define PCGRL_E_NOMEM (-4)    /* device allocation failed */
-#define PCGRL_E_DEVICE (-5)   /* the device is not a gfx950 part or does not exist */
+#define PCGRL_E_DEVICE (-5)   /* the device is not a gfx950 part, does not exist or cannot be made current */
 
 #define PCGRL_BINARY 0
 #define PCGRL_MAZE 1

@@ -416,8 +416,8 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
 
 int pcgrl_destroy(pcgrl_ctx* ctx) {
   if (!ctx) return PCGRL_OK;
-  DeviceGuard guard(ctx->device);
-  int rc = hipDeviceSynchronize() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
+  DeviceGuard guard(ctx->device);  // (freed in any case)
+  int rc = guard.ok && hipDeviceSynchronize() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
   void* bufs[] = {ctx->d_planes, ctx->d_frozen, ctx->d_env, ctx->d_metrics, ctx->d_targets, ctx->d_bad};
   for (void* b : bufs)
     if (b && hipFree(b) != hipSuccess) rc = PCGRL_E_HIP;
@@ -428,6 +428,7 @@ int pcgrl_destroy(pcgrl_ctx* ctx) {
 int pcgrl_reset(pcgrl_ctx* ctx, uint64_t seed, uint8_t* obs, void* stream) {
   if (!ctx) return PCGRL_E_NULL;
   DeviceGuard guard(ctx->device);
+  if (!guard.ok) return PCGRL_E_DEVICE;
   ctx->base.seed = seed;
   return launch_init(ctx, kInitGenerate | kInitMetrics | kInitTargets | kInitObs, seed, obs,
                      static_cast<hipStream_t>(stream));
@@ -437,6 +438,7 @@ int pcgrl_step(pcgrl_ctx* ctx, const int32_t* actions, uint8_t* obs, float* rewa
                void* stream) {
   if (!ctx || !actions) return PCGRL_E_NULL;
   DeviceGuard guard(ctx->device);
+  if (!guard.ok) return PCGRL_E_DEVICE;
   KArgs a = ctx->base;
   a.actions = actions;
   a.obs = obs;
@@ -457,6 +459,7 @@ int pcgrl_rollout(pcgrl_ctx* ctx, const int32_t* actions, int32_t n_steps, uint8
   if (n_steps < 1 || n_steps > (1 << 20)) return PCGRL_E_CONFIG;
   if (obs && (obs_slots < 1 || obs_slots > n_steps)) return PCGRL_E_CONFIG;
   DeviceGuard guard(ctx->device);
+  if (!guard.ok) return PCGRL_E_DEVICE;
   KArgs a = ctx->base;
   a.actions = actions;
   a.obs = obs;
@@ -482,6 +485,7 @@ int pcgrl_rollout(pcgrl_ctx* ctx, const int32_t* actions, int32_t n_steps, uint8
 int pcgrl_metrics(pcgrl_ctx* ctx, int32_t* out, void* stream) {
   if (!ctx || !out) return PCGRL_E_NULL;
   DeviceGuard guard(ctx->device);
+  if (!guard.ok) return PCGRL_E_DEVICE;
   const int n = ctx->cfg.batch * ctx->M;
   hipLaunchKernelGGL(copy_metrics_kernel, dim3((n + 255) / 256), dim3(256), 0,
                      static_cast<hipStream_t>(stream), static_cast<const int32_t*>(ctx->d_metrics),
@@ -492,12 +496,14 @@ int pcgrl_metrics(pcgrl_ctx* ctx, int32_t* out, void* stream) {
 int pcgrl_exact_diameter(pcgrl_ctx* ctx, int32_t* out, void* stream) {
   if (!ctx || !out) return PCGRL_E_NULL;
   DeviceGuard guard(ctx->device);
+  if (!guard.ok) return PCGRL_E_DEVICE;
   return dispatch<LaunchExact>(ctx->S, ctx->cfg.problem, ctx, ctx->base, out, static_cast<hipStream_t>(stream));
 }
 
 int pcgrl_observe(pcgrl_ctx* ctx, uint8_t* obs, void* stream) {
   if (!ctx || !obs) return PCGRL_E_NULL;
   DeviceGuard guard(ctx->device);
+  if (!guard.ok) return PCGRL_E_DEVICE;
   return launch_init(ctx, kInitObs, ctx->base.seed, obs, static_cast<hipStream_t>(stream));
 }
 
@@ -505,6 +511,7 @@ int pcgrl_get_state(pcgrl_ctx* ctx, int8_t* tiles, uint8_t* frozen, int16_t* hw,
                     int32_t* counters, void* stream) {
   if (!ctx) return PCGRL_E_NULL;
   DeviceGuard guard(ctx->device);
+  if (!guard.ok) return PCGRL_E_DEVICE;
   const int n = ctx->cfg.batch * ctx->S;
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (ctx->S == 64)
@@ -520,6 +527,7 @@ int pcgrl_set_state(pcgrl_ctx* ctx, const int8_t* tiles, const uint8_t* frozen, 
                     const int16_t* pos, void* stream) {
   if (!ctx || !tiles || !hw || !pos) return PCGRL_E_NULL;
   DeviceGuard guard(ctx->device);
+  if (!guard.ok) return PCGRL_E_DEVICE;
   const int n = ctx->cfg.batch * ctx->S;
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (ctx->S == 64)
@@ -536,6 +544,7 @@ int pcgrl_set_state(pcgrl_ctx* ctx, const int8_t* tiles, const uint8_t* frozen, 
 int pcgrl_set_targets(pcgrl_ctx* ctx, const int32_t* targets, void* stream) {
   if (!ctx || !targets) return PCGRL_E_NULL;
   DeviceGuard guard(ctx->device);
+  if (!guard.ok) return PCGRL_E_DEVICE;
   const int n = ctx->cfg.batch * ctx->M;
   hipLaunchKernelGGL(set_targets_kernel, dim3((n + 255) / 256), dim3(256), 0,
                      static_cast<hipStream_t>(stream), targets, static_cast<uint32_t*>(ctx->d_targets) + kMaxMetrics,
@@ -546,6 +555,7 @@ int pcgrl_set_targets(pcgrl_ctx* ctx, const int32_t* targets, void* stream) {
 int pcgrl_get_targets(pcgrl_ctx* ctx, int32_t* out, void* stream) {
   if (!ctx || !out) return PCGRL_E_NULL;
   DeviceGuard guard(ctx->device);
+  if (!guard.ok) return PCGRL_E_DEVICE;
   const int n = ctx->cfg.batch * ctx->M;
   hipLaunchKernelGGL(get_targets_kernel, dim3((n + 255) / 256), dim3(256), 0,
                      static_cast<hipStream_t>(stream), static_cast<const uint32_t*>(ctx->d_targets) + kMaxMetrics,
@@ -570,6 +580,7 @@ int pcgrl_num_tiles(const pcgrl_ctx* ctx) { return ctx ? ctx->K : PCGRL_E_NULL; 
 int pcgrl_bad_action_count(pcgrl_ctx* ctx, uint64_t* out, void* stream) {
   if (!ctx || !out) return PCGRL_E_NULL;
   DeviceGuard guard(ctx->device);
+  if (!guard.ok) return PCGRL_E_DEVICE;
   hipStream_t st = static_cast<hipStream_t>(stream);
   unsigned long long v = 0;
   if (hipMemcpyAsync(&v, ctx->d_bad, sizeof(v), hipMemcpyDeviceToHost, st) != hipSuccess) return PCGRL_E_HIP;
@@ -583,6 +594,7 @@ int pcgrl_selftest(int device, int32_t* mismatches) {
   int ndev = 0;
   if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) return PCGRL_E_DEVICE;
   DeviceGuard guard(device);
+  if (!guard.ok) return PCGRL_E_DEVICE;
   int32_t* d = nullptr;
   if (hipMalloc(reinterpret_cast<void**>(&d), sizeof(int32_t)) != hipSuccess) return PCGRL_E_NOMEM;
   int rc = PCGRL_OK;
