@@ -60,7 +60,7 @@ extern "C" {
 #define PCGRL_POS_RANDOM 1 /* seeded uniform position every step */
 
 #define PCGRL_REGIONS_INCREMENTAL 0 /* update the region count from floods around the edited cell */
-#define PCGRL_REGIONS_RECOUNT 1     /* flood every component again after each modifying edit */
+#define PCGRL_REGIONS_RECOUNT 1     /* count all components again after each modifying edit */
 
 #define PCGRL_OBS_STORE_AUTO 0   /* choose from the size of one step's observations */
 #define PCGRL_OBS_STORE_CACHED 1 /* ordinary stores */

@@ -438,29 +438,29 @@ __device__ __forceinline__ void nearest_two(const Lanes<S>& L, typename RowWord<
   while (more) more = trip(std::integral_constant<int, 4>{});
 }
 
-// Number of 4-connected components of `pass`: single cells without walkable neighbour are counted
-// with a popcount, every other component is flooded once from its lowest cell.
+// Number of 4-connected components of `pass`, by parallel shrinking (Levialdi's algorithm in its
+// 4-connectivity form).  One step, on every cell at once: a cell stays if its left or its lower
+// neighbour is set, and an empty cell is filled if its left, lower and lower-left neighbours all
+// are; this moves every component towards the lower left corner of its bounding box without ever
+// joining two or splitting one, until it is a single cell with no neighbour, which the next step
+// deletes.  The count is the number of such cells met on the way.  A level of h x w cells is empty
+// after h + w - 1 steps, whatever its components look like, where a flood needs one layer per edge
+// of the longest shortest path.  Steps on an empty level do nothing, so they run four to a trip.
 template <int S>
 __device__ __forceinline__ int regions_full(const Lanes<S>& L, typename RowWord<S>::T pass) {
   using W = typename RowWord<S>::T;
-  W nb = (W)(pass << 1) | (W)(pass >> 1) | L.from_above(pass) | L.from_below(pass);
-  W iso = pass & ~nb;
-  int count = L.gsum(popc(iso));
-  W R = pass & ~iso;
-  for (;;) {
-    W V = first_cell<S>(L, R);
-    if (!wave_any<S>(V != 0)) break;
-    count += L.gany(V != 0) ? 1 : 0;
-    for (;;) {
-      W V1 = L.grow(V, R);
-      W Vn = L.grow(V1, R);
-      bool ch = Vn != V1;  // a second layer that adds nothing means the flood is complete
-      V = Vn;
-      if (!wave_any<S>(ch)) break;
+  W p = pass;
+  int vanished = 0;  // this row's share of the count
+  for (int trip = 0; trip < S / 2 && wave_any<S>(p != 0); ++trip) {  // (2 S steps: more than any level needs)
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+      const W left = (W)(p << 1), below = L.from_below(p);
+      const W alone = p & ~(left | (W)(p >> 1) | below | L.from_above(p));
+      vanished += popc(alone);
+      p = (p & (left | below)) | (left & below & (W)(below << 1));
     }
-    R &= ~V;
   }
-  return count;
+  return L.gsum(vanished);
 }
 
 // Number of distinct components of `passw` (the level with the edited cell walled off) among the
