@@ -446,6 +446,67 @@ def test_degenerate_and_extreme_levels(n):
         gpu.close()
 
 
+def _rings(n):
+    """Concentric square rings of open cells, one cell wide, one wall cell apart: n // 4 components
+    nested in each other (plus a single centre cell when n % 4 is 1 or 2)."""
+    t = np.ones((n, n), np.int8)
+    for k in range(0, (n + 1) // 2, 2):
+        t[k, k:n - k] = 0
+        t[n - 1 - k, k:n - k] = 0
+        t[k:n - k, k] = 0
+        t[k:n - k, n - 1 - k] = 0
+    return t
+
+
+@pytest.mark.parametrize("n", [16, 32, 64])
+def test_full_region_count_on_nested_mirrored_and_random_levels(n):
+    """The from-scratch region count (reset, pcgrl_set_state, recount mode) on shapes that a
+    shrinking or a flooding count could get wrong in different ways: components nested inside each
+    other, the same shapes mirrored in both axes (a directional operator must not care), their
+    complements, and random maps from sparse to full, in square and ragged active areas; then
+    random edits with the count redone from scratch every step."""
+    dev = torch.device("cuda", 0)
+    rng = np.random.default_rng(1000 + n)
+    cases = []
+    rings = _rings(n)
+    for name, t in (("rings", rings), ("rings complement", 1 - rings), ("serpentine", _serpentine(n)),
+                    ("serpentine complement", 1 - _serpentine(n))):
+        for flip_name, f in (("", t), (" ud", t[::-1]), (" lr", t[:, ::-1]), (" T", t.T)):
+            cases.append((name + flip_name, np.ascontiguousarray(f).astype(np.int8), (n, n)))
+    for dens in (0.05, 0.3, 0.45, 0.55, 0.6, 0.75, 0.95, 1.0):
+        for h, w in ((n, n), (n, max(1, n // 3)), (max(1, n // 2 - 1), n), (int(rng.integers(1, n + 1)), int(rng.integers(1, n + 1)))):
+            t = np.full((n, n), -1, np.int8)
+            t[:h, :w] = (rng.random((h, w)) >= dens).astype(np.int8)   # 0 = open with probability dens
+            cases.append((f"random {dens} {h}x{w}", t, (h, w)))
+    B = len(cases)
+    cfg = wl.make_config(wl.BINARY, B, n, 5, min_size=1, autoreset=0, max_steps=10**6, pos_mode=wl.POS_RANDOM)
+    tiles = np.stack([c[1] for c in cases])
+    hw = np.array([c[2] for c in cases], np.int16)
+    pos = np.zeros((B, 2), np.int16)
+    for lpw in (0, 1):
+        gpu = binding.Pcgrl(dict(cfg, regions_mode=wl.REGIONS_RECOUNT, levels_per_wave=lpw), 0)
+        cpu = oracle.Oracle(cfg)
+        gpu.pcgrl_reset(7)
+        cpu.reset(7)
+        gpu.pcgrl_set_state(torch.from_numpy(tiles).to(dev), None, torch.from_numpy(hw).to(dev),
+                            torch.from_numpy(pos).to(dev))
+        cpu.set_state(tiles, None, hw, pos)
+        m = gpu.pcgrl_metrics().cpu().numpy()
+        assert_same("metrics", m, cpu.metrics(), "set_state")
+        nested = (n + 3) // 4                      # rings at k = 0, 2, 4, ... < (n + 1) // 2
+        assert list(m[:4, 0]) == [nested] * 4, "nested rings and their mirror images"
+        assert list(m[8:12, 0]) == [1] * 4, "a serpentine is one component however it is turned"
+        acts = wl.random_actions(cfg, 11, 3 * n, bad_fraction=0.0)
+        rew = torch.empty(B, dtype=torch.float32, device=dev)
+        for t in range(acts.shape[0]):
+            gpu.pcgrl_step(torch.from_numpy(acts[t]).to(dev), None, rew, None)
+            _, r, _ = cpu.step(acts[t])
+            assert np.array_equal(rew.cpu().numpy(), r), f"step {t}"
+        assert_same("metrics", gpu.pcgrl_metrics(), cpu.metrics(), "after edits")
+        compare_state(gpu, cpu, "after edits")
+        gpu.close()
+
+
 @pytest.mark.parametrize("n", [16, 32, 64])
 def test_long_corridors_in_maze_and_dungeon(n):
     """Player and door (and key, enemy) far apart along a serpentine corridor: path searches of
