@@ -62,7 +62,8 @@ extern "C" {
 #define PCGRL_REGIONS_INCREMENTAL 0 /* update the region count from floods around the edited cell */
 #define PCGRL_REGIONS_RECOUNT 1     /* count all components again after each modifying edit */
 
-#define PCGRL_OBS_STORE_AUTO 0   /* choose from the size of one step's observations */
+#define PCGRL_OBS_STORE_AUTO 0   /* choose from the bytes of one step's observations (pcgrl_step) or of
+                                    all the observation slots of the call (pcgrl_rollout) */
 #define PCGRL_OBS_STORE_CACHED 1 /* ordinary stores */
 #define PCGRL_OBS_STORE_STREAM 2 /* non-temporal stores */
 #define PCGRL_OBS_STORE_THROUGH 3 /* stores that write through the L2 as they are issued */
