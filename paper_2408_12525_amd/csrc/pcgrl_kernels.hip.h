@@ -576,11 +576,11 @@ __device__ __forceinline__ uint32_t control_target(const KArgs& a, uint64_t key,
 // ---------------------------------------------------------------- episodes
 
 // Start of an episode: shape, tiles, pinpoints, first position, all from the env's key.
-template <int S, int PROBLEM>
+template <int S, int PROBLEM, bool SHARED = false>
 __device__ __forceinline__ void begin_episode(const KArgs& a, const Lanes<S>& L, uint64_t key,
                                               typename RowWord<S>::T (&p)[Prob<PROBLEM>::P],
                                               typename RowWord<S>::T& fz, int& h, int& w, int& py,
-                                              int& px) {
+                                              int& px, bool restart = true, int envl = 0) {
   using W = typename RowWord<S>::T;
   using PR = Prob<PROBLEM>;
   h = a.max_h;
@@ -592,15 +592,45 @@ __device__ __forceinline__ void begin_episode(const KArgs& a, const Lanes<S>& L,
   for (int k = 0; k < 8; ++k) empty_start = empty_start && a.cdf[k] == 0;
 #pragma unroll
   for (int i = 0; i < PR::P; ++i) p[i] = 0;
-  if (!empty_start && L.y < h) {
-    for (int x = 0; x < w; ++x) {
-      uint32_t r = (uint32_t)(draw(key, 1, (uint32_t)(L.y * a.max_w + x)) >> 32);
+  auto cells = [&](uint64_t k, int x0, int x1, int dx, W (&out)[PR::P]) {  // this row's cells x0, x0+dx, ... < x1
+    for (int x = x0; x < x1; x += dx) {
+      uint32_t r = (uint32_t)(draw(k, 1, (uint32_t)(L.y * a.max_w + x)) >> 32);
       int tile = 0;  // thresholds are non-decreasing: the first one above r = how many are <= r
 #pragma unroll
-      for (int k = 0; k < PR::K - 1; ++k) tile += r >= a.cdf[k] ? 1 : 0;
+      for (int k2 = 0; k2 < PR::K - 1; ++k2) tile += r >= a.cdf[k2] ? 1 : 0;
 #pragma unroll
-      for (int i = 0; i < PR::P; ++i) p[i] |= (W)((tile >> i) & 1) << x;
+      for (int i = 0; i < PR::P; ++i) out[i] |= (W)((tile >> i) & 1) << x;
     }
+  };
+  if constexpr (SHARED && (64 / S) > 1) {
+    // Inside a step few levels of a wavefront restart at the same time, and the draws are what a
+    // restart costs: every lane group takes every G-th column of a restarting level, whichever
+    // group holds it, and the rows are put together across the groups afterwards.  Levels that
+    // restart together take turns; copies of one level are served by the same turn.
+    constexpr int G = 64 / S;
+    uint64_t todo = empty_start ? 0ull : __builtin_amdgcn_ballot_w64(restart);
+    while (todo != 0) {
+      const int src = (int)__builtin_ctzll(todo);  // a lane of the first level still to do
+      const uint64_t k = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(key >> 32), src) << 32) |
+                         (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)key, src);
+      const int kh = __builtin_amdgcn_readlane(h, src), kw = __builtin_amdgcn_readlane(w, src);
+      const int kenv = __builtin_amdgcn_readlane(envl, src);
+      W part[PR::P];
+#pragma unroll
+      for (int i = 0; i < PR::P; ++i) part[i] = 0;
+      if (L.y < kh) cells(k, L.g, kw, G, part);
+      const bool mine = restart && envl == kenv;
+#pragma unroll
+      for (int i = 0; i < PR::P; ++i) {
+        uint32_t v = (uint32_t)part[i];
+        if constexpr (S == 16) v |= (uint32_t)Lanes<S>::xor16((int)v);
+        v |= (uint32_t)__shfl_xor((int)v, 32);
+        if (mine) p[i] = (W)v;
+      }
+      todo &= ~__builtin_amdgcn_ballot_w64(mine);
+    }
+  } else {
+    if (!empty_start && L.y < h) cells(key, 0, w, 1, p);
   }
   fz = 0;
   int placed = 0;
@@ -1101,7 +1131,7 @@ __device__ __forceinline__ void obs_wave_step(const KArgs& a, const Lanes<S>& L,
     W np[PR::P], nfz;
     int nh, nw, npy, npx;
     uint64_t nkey = env_key(ra.seed, (uint64_t)wm.envl, (uint64_t)((int)er0.w + 1));
-    begin_episode<S, PROBLEM>(ra, L, nkey, np, nfz, nh, nw, npy, npx);
+    begin_episode<S, PROBLEM, true>(ra, L, nkey, np, nfz, nh, nw, npy, npx, restart, wm.envl);
     if (restart) {
 #pragma unroll
       for (int i = 0; i < PR::P; ++i) p[i] = np[i];
@@ -1184,7 +1214,7 @@ __device__ __forceinline__ void obs_wave_rollout(const KArgs& a, const Lanes<S>&
       W np[PR::P], nfz;
       int nh, nw, npy, npx;
       uint64_t nkey = env_key(ra.seed, (uint64_t)wm.envl, (uint64_t)(episode + 1));
-      begin_episode<S, PROBLEM>(ra, L, nkey, np, nfz, nh, nw, npy, npx);
+      begin_episode<S, PROBLEM, true>(ra, L, nkey, np, nfz, nh, nw, npy, npx, restart, wm.envl);
       if (restart) {
 #pragma unroll
         for (int i = 0; i < PR::P; ++i) p[i] = np[i];
@@ -1450,7 +1480,7 @@ __global__ __launch_bounds__(MODE == kModeSplit || MODE == kModeRolloutSplit ? 3
       W np[PR::P], nfz;
       int nh, nw, npy, npx;
       uint64_t nkey = env_key(ra.seed, (uint64_t)wm.envl, (uint64_t)(er.episode + 1));
-      begin_episode<S, PROBLEM>(ra, L, nkey, np, nfz, nh, nw, npy, npx);
+      begin_episode<S, PROBLEM, true>(ra, L, nkey, np, nfz, nh, nw, npy, npx, restart, wm.envl);
       W ninside = inside_row<W>(L.y, nh, nw);
       int nm[PR::M];
       full_metrics<S, PROBLEM>(L, np, ninside, restart, nm);

@@ -507,6 +507,23 @@ def test_full_region_count_on_nested_mirrored_and_random_levels(n):
         gpu.close()
 
 
+@pytest.mark.parametrize("problem,n", [(wl.MAZE, 16), (wl.BINARY, 16), (wl.DUNGEON, 32), (wl.BINARY, 32), (wl.MAZE, 64)])
+def test_episodes_that_end_at_different_steps(problem, n):
+    """A small change limit ends every level's episode at a step of its own, so that in most
+    steps one level of a wavefront restarts while its neighbours go on (a restarting level's cells
+    are then drawn by all the lane groups of its wavefront together), now and then two or all of
+    them at once; every launch shape, random shapes and pinpoints, single steps and a rollout."""
+    base = wl.make_config(problem, 150, n, 9, min_size=max(3, n // 3), n_frozen=2, max_changes=4,
+                          max_steps=37, pos_mode=wl.POS_RANDOM)
+    shapes = [dict(levels_per_wave=0, split_step=0), dict(levels_per_wave=1, split_step=1),
+              dict(levels_per_wave=2, split_step=2), dict(levels_per_wave=4, split_step=2, split_obs_levels=1),
+              dict(levels_per_wave=4, split_step=1)]
+    for k, shape in enumerate(shapes):
+        cfg = dict(base, **shape)
+        run_parity(cfg, 45, seed=50 + k, aseed=60 + k, label=f"staggered {shape}")
+        _rollout_against_oracle(cfg, 45, 45, 70 + k)
+
+
 @pytest.mark.parametrize("n", [16, 32, 64])
 def test_long_corridors_in_maze_and_dungeon(n):
     """Player and door (and key, enemy) far apart along a serpentine corridor: path searches of
