@@ -108,6 +108,8 @@ def main():
     ap.add_argument("--max-changes", type=int, default=None, metavar="N",
                     help="end an episode after N modifying edits as well (episodes then end, and "
                          "levels restart, at different steps; default: the workload's own setting)")
+    ap.add_argument("--obs-store", choices=["auto", "cached", "stream", "through"], default="auto",
+                    help="how observations are stored (default: the library's own rule)")
     ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
                     help="replay a HIP graph of pcgrl_step launches (default) or call it from Python")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
@@ -137,6 +139,7 @@ def main():
 
     cfg = wl.workload(args.workload, batch=args.batch)
     cfg["regions_mode"] = wl.REGIONS_RECOUNT if args.regions == "recount" else wl.REGIONS_INCREMENTAL
+    cfg["obs_store_mode"] = ["auto", "cached", "stream", "through"].index(args.obs_store)
     if args.max_changes is not None:
         cfg["max_changes"] = args.max_changes
     K = args.steps if args.steps is not None else cfg["max_steps"]
@@ -214,7 +217,7 @@ def main():
                    "batch": B, "map": f"{cfg['max_h']}x{cfg['max_w']}",
                    "min_map": f"{cfg['min_h']}x{cfg['min_w']}", "obs_w": cfg["obs_w"],
                    "obs_bytes_per_env": wl.obs_bytes(cfg), "n_frozen": cfg["n_frozen"],
-                   "regions": args.regions, "max_changes": cfg.get("max_changes", 0), "launch": args.launch, "launches_per_step": 1, "reps": args.reps,
+                   "regions": args.regions, "max_changes": cfg.get("max_changes", 0), "obs_store": args.obs_store, "launch": args.launch, "launches_per_step": 1, "reps": args.reps,
                    "algorithmic_bytes_per_env_step": abytes},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_from_profiles(tag),

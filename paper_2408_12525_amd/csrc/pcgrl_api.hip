@@ -380,8 +380,10 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   // is the whole ring of observation slots it writes: while that fits the last-level cache, ordinary
   // stores (equal to or up to 6 % ahead of the others at every batch tried); beyond it, ordinary
   // stores for large observations (maze16, a slot per step: 4.4 against 4.9 us per step; maze64
-  // 11.0 against 11.8) and non-temporal ones for small ones (binary16 3.0 against 3.2, dungeon32
-  // 9.5 against 10.4).  Decided per pcgrl_rollout call, which knows the number of slots.
+  // 11.0 against 11.8) and for 16-row levels (binary16 at 65 536: 2.1e9 against 2.0e9 steps/s once
+  // neighbouring level groups share an L2, which is what a rollout with ordinary stores does),
+  // non-temporal ones for the small observations of 32-row levels (dungeon32 9.5 against 10.4).
+  // Decided per pcgrl_rollout call, which knows the number of slots.
   {
     const size_t obs_step_bytes = (size_t)cfg->batch * E;
     const size_t MB = (size_t)1 << 20;
@@ -471,8 +473,9 @@ int pcgrl_rollout(pcgrl_ctx* ctx, const int32_t* actions, int32_t n_steps, uint8
     a.stream_obs = ctx->store_roll;
   } else {
     const size_t ring = (size_t)a.obs_slots * (size_t)ctx->cfg.batch * ctx->obs_bytes;
-    a.stream_obs = (ring <= ((size_t)448 << 20) || ctx->obs_bytes >= 3072) ? kStoreCached : kStoreStream;
+    a.stream_obs = (ring <= ((size_t)448 << 20) || ctx->obs_bytes >= 3072 || ctx->S == 16) ? kStoreCached : kStoreStream;
   }
+  a.by_die = a.stream_obs == kStoreCached ? 1 : 0;
   if (obs && ctx->split_roll) {
     auto lg2 = [](int v) { return v == 4 ? 2 : v == 2 ? 1 : 0; };
     a.envs_per_wave_log2 = lg2(ctx->roll_m) | (lg2(ctx->roll_o) << 8);

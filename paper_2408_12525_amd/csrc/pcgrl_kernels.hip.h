@@ -68,6 +68,7 @@ struct KArgs {
   int32_t obs_packed;     // non-zero: bit-packed observation format
   int32_t obs_frozen_channel;  // non-zero: a last channel marks the pinpoint cells in view
   int32_t stream_obs;     // how observations are stored: kStoreCached / kStoreStream / kStoreThrough
+  int32_t by_die;       // rollouts: consecutive level groups run on the same die (see level_group_of_block)
   int32_t flags;          // init kernel only
   int32_t rollout_steps;  // rollout kernel: steps per launch
   int32_t obs_slots;      // rollout kernel: step t writes observation slot t % obs_slots
@@ -922,6 +923,26 @@ __device__ __forceinline__ void store_metrics(int32_t* dst, const int (&m)[Prob<
   }
 }
 
+// Workgroups are handed to the eight accelerator dies (each with an L2 of its own) in turn, so
+// workgroups b and b + 1 never share an L2, while the output regions of neighbouring level groups
+// share the cache line on which one ends and the next begins (an observation is seldom a multiple
+// of 128 bytes).  Written through two L2s, such a line reaches memory as two partial writes, and
+// measured on plain stores that costs a quarter to a half of the write rate (regions of 9610 bytes:
+// 4.2 against 5.6 TB/s; of 1922 bytes: 3.2 against 6.3).  So die x takes a contiguous run of level
+// groups: the blocks b = x, x + 8, x + 16, ... work on consecutive groups, and both halves of a
+// shared line meet in one L2.  A bijection on 0 .. n-1 for every n.  Used by rollouts that store
+// with ordinary stores (maze16 at a batch of 65 536: +12 % steps per second, binary16 +7 %, maze64
+// and binary32 with the 63-cell window +6 %; with non-temporal stores, which do not wait in the L2,
+// it costs the dungeon 4 %).  A launch per step is better off with blocks in their natural order,
+// whatever the store kind (measured: maze16 6.2 against 5.7 us, maze64 18.1 against 17.1): blocks
+// that run at the same time then write neighbouring addresses.
+template <bool ROLLOUT> __device__ __forceinline__ int level_group_of_block(int by_die) {
+  const int b = (int)blockIdx.x, n = (int)gridDim.x;
+  if constexpr (!ROLLOUT) return b;
+  const int x = b & 7, q = n >> 3, rem = n & 7;
+  return by_die ? x * q + min(x, rem) + (b >> 3) : b;
+}
+
 // Which wavefront, which levels: shared prologue of the two kernels.
 template <int S> struct WaveMap {
   int wave, env0, nvalid, env, envl;
@@ -971,7 +992,7 @@ __global__ __launch_bounds__(64) void init_kernel(KArgs a) {
   extern __shared__ uint32_t lds_all[];
   Lanes<S> L;
   WaveMap<S> wm;
-  wm.init(a, L, lds_all, (int)blockIdx.x, a.envs_per_wave_log2 & 0xff);
+  wm.init(a, L, lds_all, level_group_of_block<false>(0), a.envs_per_wave_log2 & 0xff);
   W* planes = reinterpret_cast<W*>(a.planes);
   W* frozen = reinterpret_cast<W*>(a.frozen);
   const size_t ridx = (size_t)wm.envl * S + L.y;
@@ -1038,7 +1059,7 @@ __global__ __launch_bounds__(64) void exact_diameter_kernel(KArgs a, int32_t* ou
   extern __shared__ uint32_t lds_all[];
   Lanes<S> L;
   WaveMap<S> wm;
-  wm.init(a, L, lds_all, (int)blockIdx.x, a.envs_per_wave_log2 & 0xff);
+  wm.init(a, L, lds_all, level_group_of_block<false>(0), a.envs_per_wave_log2 & 0xff);
   const W* planes = reinterpret_cast<const W*>(a.planes);
   const size_t ridx = (size_t)wm.envl * S + L.y;
   W p[PR::P];
@@ -1261,7 +1282,7 @@ __global__ __launch_bounds__(MODE == kModeSplit || MODE == kModeRolloutSplit ? 3
                  "s"(a.obs_frozen_channel), "s"(a.stream_obs));
   Lanes<S> L;
   WaveMap<S> wm;
-  wm.init(a, L, lds_all, (int)blockIdx.x, a.envs_per_wave_log2 & 0xff);
+  wm.init(a, L, lds_all, level_group_of_block<ROLL>(a.by_die), a.envs_per_wave_log2 & 0xff);
   // SPLIT: the workgroup is two wavefronts on the same levels; wavefront 0 does the metrics, the
   // reward and the state stores (the code below, without its observation parts), wavefront 1 the
   // observation; both load the same (old) state
@@ -1271,7 +1292,7 @@ __global__ __launch_bounds__(MODE == kModeSplit || MODE == kModeRolloutSplit ? 3
     const int wid = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     if (wid != 0) {
       const int lg = a.envs_per_wave_log2 & 0xff, lgo = (a.envs_per_wave_log2 >> 8) & 0xff;
-      wm.init(a, L, lds_all + (wid - 1) * a.obs_lds_words, ((int)blockIdx.x << (lg - lgo)) + wid - 1, lgo);
+      wm.init(a, L, lds_all + (wid - 1) * a.obs_lds_words, (level_group_of_block<ROLL>(a.by_die) << (lg - lgo)) + wid - 1, lgo);
       if constexpr (ROLL) obs_wave_rollout<S, PROBLEM>(a, L, wm);
       else obs_wave_step<S, PROBLEM>(a, L, wm);
       __builtin_amdgcn_endpgm();  // (not a return: the two paths must not meet again, or the
