@@ -188,8 +188,8 @@ int pcgrl_rollout(pcgrl_ctx* ctx, const int32_t* actions, int32_t n_steps, uint8
 int pcgrl_metrics(pcgrl_ctx* ctx, int32_t* out, void* stream);
 
 /* Exact diameter of every level: the largest shortest-path distance between any two connected
- * walkable cells (Task / Binary domain: "the longest shortest path between any two points"), by a
- * breadth-first sweep from every walkable cell.  A diagnostic for the error of the two-sweep
+ * walkable cells (the graph diameter that the two-sweep estimate of Task / Binary domain stands
+ * for), by a breadth-first sweep from every walkable cell.  A diagnostic for the error of the two-sweep
  * estimate, not part of a step: the cost grows with (walkable cells) x (eccentricity), about a
  * million vector instructions for one open 64x64 level.  out: device, int32 [batch]. */
 int pcgrl_exact_diameter(pcgrl_ctx* ctx, int32_t* out, void* stream);

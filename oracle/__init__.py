@@ -81,6 +81,7 @@ def lib():
         L.orc_env_key.argtypes = [C.c_uint64] * 3
         L.orc_draw.restype = C.c_uint64
         L.orc_draw.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32]
+        L.orc_below.argtypes = [C.c_uint32, C.c_int]
         L.orc_regions.argtypes = [p, C.c_int, C.c_int, C.c_int]
         L.orc_bfs.argtypes = [p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, p]
         L.orc_diameter_two_pass.argtypes = [p, C.c_int, C.c_int, C.c_int]
@@ -262,3 +263,7 @@ def env_key(seed, env, episode) -> int:
 
 def draw(key, stream, counter) -> int:
     return lib().orc_draw(C.c_uint64(key), C.c_uint32(stream), C.c_uint32(counter))
+
+
+def below(r, n) -> int:
+    return lib().orc_below(C.c_uint32(r), int(n))

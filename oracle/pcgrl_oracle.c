@@ -104,6 +104,7 @@ static uint32_t hi32(uint64_t u) { return (uint32_t)(u >> 32); }
 static uint32_t lo32(uint64_t u) { return (uint32_t)u; }
 /* uniform integer in [0, n) from 32 random bits: multiply and keep the high word */
 static int below(uint32_t r, int n) { return (int)(((uint64_t)r * (uint64_t)n) >> 32); }
+int orc_below(uint32_t r, int n) { return below(r, n); }
 
 /* ------------------------------------------------------ graph primitives */
 
@@ -202,8 +203,9 @@ int orc_diameter_two_pass(const int8_t* tiles, int h, int w, int pitch) {
   return far;
 }
 
-/* Binary domain: "the longest shortest path between any two points in the maze", computed
- * exactly: one breadth-first search from every walkable cell, the largest distance found. */
+/* Task / Binary domain: the graph diameter of the walkable cells (the quantity the two-sweep
+ * estimate stands for), computed exactly: one breadth-first search from every walkable cell,
+ * the largest distance found. */
 int orc_exact_diameter(const int8_t* tiles, int h, int w, int pitch) {
   static __thread int32_t dist[MAXC];
   int best = 0;

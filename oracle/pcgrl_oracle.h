@@ -16,10 +16,19 @@
  *   regions, BFS distances, two-pass diameter, maze / dungeon path lengths,
  *   nearest enemy, tile counts, reward, observation, scan order, frozen
  *   tiles                      -> pinned (brute force, closed forms, invariants)
- *   mix64                      -> pinned (published splitmix64 output sequence)
- *   key / draw derivation, the default weights and target table, the chest
- *   tile of the 7-tile dungeon -> parity unpinned (no external fixed point
- *   exists; the paper leaves them to code bases that are not reproduced here)
+ *   mix64, draw, env_key       -> pinned (published splitmix64 output sequence:
+ *                                 draw(key, 0, i) is output i+1 of that generator
+ *                                 seeded with key, a stream shifts the seed, and
+ *                                 the inner hash of env_key is output env+1 of
+ *                                 the generator seeded with the seed)
+ *   below, and which stream / counter / half-word each draw of an episode
+ *   uses                       -> pinned (hand-computed cases; the episode's
+ *                                 shape, tiles, pinpoints, positions and control
+ *                                 targets rebuilt in the tests from draw alone)
+ *   the episode multiplier of env_key, the default weights and target table,
+ *   the chest tile of the 7-tile dungeon -> parity unpinned (this build's own
+ *   choices: no external fixed point exists; the paper leaves them to code
+ *   bases that are not reproduced here)
  */
 #ifndef PCGRL_ORACLE_H
 #define PCGRL_ORACLE_H
@@ -102,6 +111,7 @@ void orc_get_targets(const orc_ctx* ctx, int32_t* targets /* [batch][M][2] */);
 uint64_t orc_mix64(uint64_t z);
 uint64_t orc_env_key(uint64_t seed, uint64_t env, uint64_t episode);
 uint64_t orc_draw(uint64_t key, uint32_t stream, uint32_t counter);
+int orc_below(uint32_t r, int n); /* uniform integer in [0, n) from 32 random bits */
 /* all on one level: tiles int8 [h][w] with row pitch `pitch` */
 int orc_regions(const int8_t* tiles, int h, int w, int pitch);
 /* dist int32 [h][w] (pitch w): edges from the nearest cell whose tile == src_tile

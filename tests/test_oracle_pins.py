@@ -25,12 +25,124 @@ def test_mix64_reproduces_published_splitmix64_sequence():
     assert got == want
 
 
+# The published splitmix64 outputs for the seed 1234567 (same vector as above).
+_SEED = 1234567
+_PUBLISHED = [6457827717110365317, 3203168211198807973, 9817491932198370423,
+              4593380528125082431, 16408922859458223821]
+_GOLDEN = 0x9E3779B97F4A7C15
+_MASK = 2**64 - 1
+
+
+def test_draw_is_the_published_splitmix64_sequence_of_its_key():
+    # draw(key, 0, i) is defined as output number i+1 of the published generator seeded with
+    # key, so the printed reference vector pins it directly: a dropped "+1", a wrong increment
+    # or a counter in the wrong place gives other numbers.
+    assert [oracle.draw(_SEED, 0, i) for i in range(5)] == _PUBLISHED
+    # A stream is the same generator started (stream << 32) outputs further on, i.e. from the
+    # seed key + golden * (stream << 32).  Choosing the key so that this lands on 1234567 must
+    # reproduce the printed vector in every stream, and different streams of one key differ.
+    for stream in (1, 2, 3, 4, 7):
+        key = (_SEED - _GOLDEN * (stream << 32)) & _MASK
+        assert [oracle.draw(key, stream, i) for i in range(5)] == _PUBLISHED, stream
+        assert oracle.draw(key, 0, 0) != _PUBLISHED[0]
+    first = [oracle.draw(99, s, 0) for s in range(5)]
+    assert len(set(first)) == 5
+
+
+def test_env_key_is_built_on_the_published_sequence():
+    # The inner hash of the key, mix64(seed + golden * (env + 1)), is output env+1 of the
+    # published generator seeded with `seed`; the episode enters by an XOR with a multiple of
+    # the episode constant before the (pinned) mixing function is applied again.
+    EPISODE = 0xD1B54A32D192ED03
+    for env in range(5):
+        for ep in (0, 1, 2, 1000):
+            want = oracle.mix64(_PUBLISHED[env] ^ ((EPISODE * (ep + 1)) & _MASK))
+            assert oracle.env_key(_SEED, env, ep) == want, (env, ep)
+    # env and episode are not interchangeable, and env 0 / episode 0 are not the raw seed
+    assert oracle.env_key(_SEED, 1, 0) != oracle.env_key(_SEED, 0, 1)
+    assert oracle.env_key(_SEED, 0, 0) not in (_SEED, _PUBLISHED[0])
+
+
+def test_below_on_hand_computed_cases():
+    # uniform integer in [0, n): the high word of r * n, r a 32-bit draw
+    assert oracle.below(0, 25) == 0
+    assert oracle.below(2**31, 24) == 12            # exactly half way
+    assert oracle.below(2**31, 25) == 12            # 12.5 rounds down
+    assert oracle.below(2**32 - 1, 25) == 24        # the largest draw stays below n
+    assert oracle.below(2**32 - 1, 1) == 0
+    assert oracle.below(3 * 2**30, 64) == 48        # three quarters
+    assert oracle.below(2**30 - 1, 64) == 15        # just under a quarter
+    assert oracle.below(2**30, 64) == 16
+    # each value of [0, n) owns an equal share of the 2^32 draws (to within one)
+    for n in (3, 7, 25, 64):
+        edges = [min(r for r in (k * 2**32 // n - 1, k * 2**32 // n, k * 2**32 // n + 1)
+                     if r >= 0 and oracle.below(r, n) == k) for k in range(n)]
+        assert all(abs(edges[k] - k * 2**32 / n) <= 1 for k in range(n))
+
+
+def test_an_episode_uses_the_streams_counters_and_half_words_it_should():
+    # Everything an episode draws, rebuilt here from draw() alone (pinned above) with Python
+    # integers: shape from stream 0 (counter 0 height, 1 width; high word), tiles from stream 1
+    # (counter y * max_w + x; high word against the cumulative thresholds), pinpoints from
+    # stream 2 (counter = attempt; high word row, low word column; occupied cells are skipped),
+    # positions from stream 3 (counter = step count; high word row, low word column), control
+    # targets from stream 4 (counter = metric index; high word).  A swapped stream, a shifted
+    # counter or the wrong half of a draw inside the oracle's episode code fails here.
+    cfg = wl.make_config(wl.DUNGEON, 5, 12, 5, min_size=6, max_w=14, min_w=9, n_frozen=3,
+                         max_steps=6, probs=[.3, .3, .08, .08, .08, .08, .08],
+                         ctrl={1: (10, 60), 2: (2, 9)})
+    seed = 77
+    env = oracle.Oracle(cfg)
+    env.reset(seed, want_obs=False)
+    cdf = cfg["init_cdf"]
+    hi = lambda u: u >> 32
+    lo = lambda u: u & 0xFFFFFFFF
+    mulhi = lambda r, n: (r * n) >> 32
+
+    def expect_episode(e, ep):
+        key = oracle.env_key(seed, e, ep)
+        h = cfg["min_h"] + mulhi(hi(oracle.draw(key, 0, 0)), cfg["max_h"] - cfg["min_h"] + 1)
+        w = cfg["min_w"] + mulhi(hi(oracle.draw(key, 0, 1)), cfg["max_w"] - cfg["min_w"] + 1)
+        tiles = np.full((cfg["max_h"], cfg["max_w"]), -1, np.int8)
+        for y in range(h):
+            for x in range(w):
+                r = hi(oracle.draw(key, 1, y * cfg["max_w"] + x))
+                tiles[y, x] = sum(1 for k in range(6) if r >= cdf[k])
+        frozen, att = [], 0
+        while len(frozen) < 3:
+            u = oracle.draw(key, 2, att)
+            att += 1
+            cell = (mulhi(hi(u), h), mulhi(lo(u), w))
+            if cell not in frozen:
+                frozen.append(cell)
+        tg = {i: a + mulhi(hi(oracle.draw(key, 4, i)), b - a + 1) for i, (a, b) in {1: (10, 60), 2: (2, 9)}.items()}
+        return key, h, w, tiles, frozen, tg
+
+    def check(ep, t):
+        st, tg = env.get_state(), env.get_targets()
+        for e in range(env.B):
+            key, h, w, tiles, frozen, want_tg = expect_episode(e, ep)
+            assert tuple(st["hw"][e]) == (h, w)
+            if t == 0:
+                assert (st["tiles"][e] == tiles).all()
+            assert sorted(zip(*np.nonzero(st["frozen"][e]))) == sorted(frozen)
+            u = oracle.draw(key, 3, t)
+            assert tuple(st["pos"][e]) == (mulhi(hi(u), h), mulhi(lo(u), w)), (e, ep, t)
+            assert all(tuple(tg[e, i]) == (v, v) for i, v in want_tg.items())
+
+    check(0, 0)
+    nothing = np.full(env.B, -1, np.int32)                     # out-of-range action: no edit
+    for step in range(1, 14):
+        env.step(nothing, want_obs=False)
+        check(step // 6, step % 6)
+
+
 def test_keys_and_draws_do_not_collide():
     keys = {oracle.env_key(7, e, ep) for e in range(64) for ep in range(8)}
     assert len(keys) == 64 * 8
     k = oracle.env_key(7, 3, 0)
-    draws = {oracle.draw(k, s, c) for s in range(4) for c in range(4096)}
-    assert len(draws) == 4 * 4096
+    draws = {oracle.draw(k, s, c) for s in range(5) for c in range(4096)}
+    assert len(draws) == 5 * 4096
     assert oracle.env_key(7, 3, 0) != oracle.env_key(8, 3, 0)
 
 
