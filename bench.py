@@ -6,6 +6,10 @@ observation of every level, one kernel launch.  Inputs (levels, pre-generated ra
 resident in HBM before the timed region starts.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--batch B]
+
+The headline workload is the 64x64 maze at a batch of 8192 (the configuration the bandwidth
+target is quoted on); the `configs` object of the same line carries every other workload, and the
+16x16 binary problem at a batch of 262 144 (the point the steps-per-second target is read at).
 """
 from __future__ import annotations
 
@@ -20,20 +24,45 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+# plain integer vector work: 256 compute units x 4 SIMDs, one wave64 instruction per 4 cycles
+# each, 2.4 GHz  ->  wave-instructions per second the chip can issue
+VALU_PEAK_GINST = 256 * 4 * 2.4 / 4.0
+MIN_REP_MS = 5.0       # a timed repetition lasts at least this long (the graph is replayed)
+MALL_BYTES = 256 << 20  # memory-side cache: an observation ring has to be well beyond it
+
+
+def state_bytes_per_env(cfg) -> int:
+    """Bytes of one level's resident state that a step reads: the tile code as bit-planes (P planes
+    of S rows of S bits, S = 16 / 32 / 64 covering the buffer), the 32-byte record, and its rows of
+    the metric cache and the target ranges."""
+    from paper_2408_12525_amd import workloads as wl
+    side = max(cfg["max_h"], cfg["max_w"])
+    S = 16 if side <= 16 else 32 if side <= 32 else 64
+    P = {wl.BINARY: 1, wl.MAZE: 2, wl.DUNGEON: 3}[cfg["problem"]]
+    M = wl.num_metrics(cfg["problem"])
+    return P * S * (8 if S == 64 else 4) + 32 + 4 * M + 4 * M
 
 
 def algorithmic_bytes_per_env_step(cfg) -> int:
-    """What one step of one level must move: write the observation, reward and done flag, read the
-    action and the level once (canonical int8 grid), write back one cell, the metric cache and the
-    counters."""
+    """What one step of one level must move, with the level kept as bit-planes: read the state
+    (planes, record, metric cache, target ranges) and the action; write the observation, the reward
+    and the done flag, the record, and - after a modifying edit - one row of each plane and the
+    metric cache."""
     from paper_2408_12525_amd import workloads as wl
     M = wl.num_metrics(cfg["problem"])
-    return wl.obs_bytes(cfg) + cfg["max_h"] * cfg["max_w"] + 4 + 4 + 1 + 1 + 4 * M + 16
+    return wl.obs_bytes(cfg) + state_bytes_per_env(cfg) + 4 + 4 + 1 + 32 + 4 * M
 
 
-def traffic_from_profiles(tag: str):
-    """HBM bytes per launch measured with rocprofv3 counters, if a summary was committed."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+def rollout_bytes_per_env_step(cfg) -> int:
+    """A resident rollout moves per step only the action in and observation, reward, done out."""
+    from paper_2408_12525_amd import workloads as wl
+    return wl.obs_bytes(cfg) + 4 + 4 + 1
+
+
+def profile_table(fname: str, tag: str):
+    """Second column of the line of profiles/<fname> that starts with `tag` (figures taken with
+    rocprofv3 and committed there), or None."""
+    path = os.path.join(ROOT, "profiles", fname)
     if not os.path.exists(path):
         return None
     for line in open(path):
@@ -46,17 +75,30 @@ def traffic_from_profiles(tag: str):
     return None
 
 
-def cpu_baseline(cfg, seed, aseed, budget_s=12.0):
-    """The CPU oracle as it stands, on a bounded sample of the same workload, sharded over the
-    host threads this process may use (environments are independent)."""
+def cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(cfg, seed, aseed):
+    """The CPU oracle as it stands on a bounded sample of the same workload: one core on 256
+    levels x 200 steps, then the same sample per thread sharded over the host threads this process
+    may use (environments are independent)."""
     import numpy as np
     from concurrent.futures import ThreadPoolExecutor
     import oracle
     from paper_2408_12525_amd import workloads as wl
 
     threads = max(1, min(16, len(os.sched_getaffinity(0))))
-    envs = min(cfg["batch"], 32 * threads)
-    steps = 100
+    per = 256
+    steps = 200
+    envs = min(cfg["batch"], per * threads)
+    threads = max(1, min(threads, envs // per)) if envs >= per else 1
     scfg = dict(cfg, batch=envs)
     env = oracle.Oracle(scfg)
     env.reset(seed, want_obs=False)
@@ -71,29 +113,228 @@ def cpu_baseline(cfg, seed, aseed, budget_s=12.0):
         for t in range(steps):
             env.step_range(lo, hi, acts[t], obs, rew, done)
 
-    # one core
     t0 = time.perf_counter()
-    n1 = 0
-    lo, hi = bounds[0]
-    for t in range(steps):
-        env.step_range(lo, hi, acts[t], obs, rew, done)
-        n1 += hi - lo
-        if time.perf_counter() - t0 > budget_s / 3:
-            break
-    one = n1 / (time.perf_counter() - t0)
-    # all threads (fresh episode so that every shard does the same work)
-    env.reset(seed, want_obs=False)
+    shard(bounds[0])                       # one core: the first shard, all its steps
+    one_dt = time.perf_counter() - t0
+    one = (bounds[0][1] - bounds[0][0]) * steps / one_dt
+    env.reset(seed, want_obs=False)        # fresh episode so that every shard does the same work
     t0 = time.perf_counter()
     with ThreadPoolExecutor(threads) as ex:
         list(ex.map(shard, bounds))
     dt = time.perf_counter() - t0
     return {
         "value": envs * steps / dt, "unit": "env-steps/s", "cores": threads, "kind": "oracle",
-        "value_1core": one,
+        "value_1core": one, "cpu_model": cpu_model(),
         "sample": f"{envs} envs x {steps} steps of the same workload from the same seed "
                   f"(observation written every step), {threads} threads; 1-core figure on "
-                  f"{hi - lo} envs",
+                  f"{bounds[0][1] - bounds[0][0]} envs x {steps} steps ({one_dt:.1f} s)",
     }
+
+
+class GpuRun:
+    """One workload on the GPU: a context, its buffers, and the two timed legs."""
+
+    def __init__(self, name, batch, args):
+        import torch
+        from paper_2408_12525_amd import binding, workloads as wl
+        self.torch, self.wl = torch, wl
+        cfg = wl.workload(name, batch=batch)
+        cfg["regions_mode"] = wl.REGIONS_RECOUNT if args.regions == "recount" else wl.REGIONS_INCREMENTAL
+        cfg["obs_store_mode"] = ["auto", "cached", "stream", "through"].index(args.obs_store)
+        if args.max_changes is not None:
+            cfg["max_changes"] = args.max_changes
+        cfg["obs_pitch"] = -1 if args.obs_pitch == "lines" else 0
+        self.cfg, self.name, self.args = cfg, name, args
+        self.B = cfg["batch"]
+        self.tag = f"{name}_B{self.B}"
+        self.dev = torch.device("cuda", 0)
+        self.env = binding.Pcgrl(cfg, 0)
+        self.obs_env_bytes = wl.obs_bytes(cfg)        # the observation itself
+        self.obs_stride = self.env.obs_stride          # what one level takes in an obs buffer
+        self.rew = torch.empty(self.B, dtype=torch.float32, device=self.dev)
+        self.done = torch.empty(self.B, dtype=torch.uint8, device=self.dev)
+
+    def close(self):
+        self.env.close()
+
+    def obs_ring(self, want_slots, cap_bytes=16 << 30):
+        """[slots, B, ...] observation buffers: a slot per step, as a learner that keeps its rollout
+        has, and more of them than the memory-side cache holds, so that every byte written has to
+        reach HBM (a single buffer rewritten every step would stay in that cache)."""
+        one = self.B * self.obs_stride
+        slots = max(1, min(want_slots, cap_bytes // max(1, one)))
+        return self.torch.empty((slots,) + tuple(self.env.obs_shape), dtype=self.torch.uint8, device=self.dev)
+
+    def per_step(self, K, W, reps, seed=0, aseed=1):
+        """K pcgrl_step launches, replayed from a HIP graph (each launch a kernel node with its own
+        slice of the action stream and its own observation slot); a repetition replays the graph
+        until it has lasted MIN_REP_MS.  Returns wall and HIP-event time per step."""
+        torch, wl, env, args = self.torch, self.wl, self.env, self.args
+        n_act = min(K, 1000)   # the action stream repeats after 1000 steps (keeps it small in HBM)
+        acts = torch.from_numpy(wl.random_actions(self.cfg, aseed, n_act)).to(self.dev)
+        warm = torch.from_numpy(wl.random_actions(self.cfg, aseed + 1, max(W, 1))).to(self.dev)
+        chunk = min(n_act, K)
+        while K % chunk:
+            chunk -= 1
+        one = self.B * self.obs_stride
+        slots = 1 if args.obs_ring == "one" else max(1, min(chunk, -(-4 * MALL_BYTES // one)))
+        ring = self.obs_ring(slots)
+        slots = ring.shape[0]
+        graph = None
+        if args.launch == "graph":
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                env.pcgrl_reset(seed, ring[0])
+                with torch.cuda.graph(graph, stream=side):
+                    for t in range(chunk):
+                        env.pcgrl_step(acts[t], ring[t % slots], self.rew, self.done)
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+
+        def run_once():
+            if graph is not None:
+                for _ in range(K // chunk):
+                    graph.replay()
+            else:
+                for t in range(K):
+                    env.pcgrl_step(acts[t % n_act], ring[t % slots], self.rew, self.done)
+
+        times_ms, ev_ms, rounds = [], [], 1
+        for rep in range(reps):
+            env.pcgrl_reset(seed, ring[0])
+            for t in range(W):
+                env.pcgrl_step(warm[t], ring[t % slots], self.rew, self.done)
+            if rep == 0:               # how many rounds of K steps make a repetition long enough
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                run_once()
+                torch.cuda.synchronize()
+                est_ms = (time.perf_counter() - t0) * 1e3
+                rounds = max(1, int(-(-MIN_REP_MS // max(est_ms, 1e-3))))
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            e0.record()                      # on the current stream, the one the steps run on
+            for _ in range(rounds):
+                run_once()
+            e1.record()
+            torch.cuda.synchronize()
+            times_ms.append((time.perf_counter() - t0) * 1e3)
+            ev_ms.append(e0.elapsed_time(e1))
+        order = sorted(range(reps), key=lambda i: times_ms[i])
+        mid = order[len(order) // 2]
+        n = K * rounds
+        del ring
+        return {"wall_ms_per_step": times_ms[mid] / n, "event_ms_per_step": ev_ms[mid] / n,
+                "timed_steps": n, "obs_slots": slots}
+
+    def rollout(self, K, T=100, seed=0, aseed=1):
+        """The same steps through pcgrl_rollout: T steps per launch, the levels resident in registers
+        in between; every step still writes its observation (a slot per step), reward and done."""
+        torch, wl, env = self.torch, self.wl, self.env
+        T = max(1, min(T, K))
+        launches = max(1, K // T)
+        racts = torch.from_numpy(wl.random_actions(self.cfg, aseed, T)).to(self.dev)
+        robs = self.obs_ring(T)
+        slots = robs.shape[0]
+        rrew = torch.empty((T, self.B), dtype=torch.float32, device=self.dev)
+        rdone = torch.empty((T, self.B), dtype=torch.uint8, device=self.dev)
+        env.pcgrl_reset(seed, robs[0])
+        env.pcgrl_rollout(racts, robs, rrew, rdone)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        env.pcgrl_rollout(racts, robs, rrew, rdone)
+        torch.cuda.synchronize()
+        est_ms = (time.perf_counter() - t0) * 1e3
+        launches = max(launches, int(-(-MIN_REP_MS // max(est_ms, 1e-3))))
+        r0 = torch.cuda.Event(enable_timing=True)
+        r1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        r0.record()
+        for _ in range(launches):
+            env.pcgrl_rollout(racts, robs, rrew, rdone)
+        r1.record()
+        torch.cuda.synchronize()
+        rwall = time.perf_counter() - t0
+        ev_s = r0.elapsed_time(r1) * 1e-3
+        del robs
+        return {"wall_s_per_step": rwall / (T * launches), "event_s_per_step": ev_s / (T * launches),
+                "steps_per_launch": T, "launches": launches, "obs_slots": slots}
+
+
+def store_rates(torch, binding, region_bytes, total=6 << 30):
+    """What the memory system takes as a pure write stream, from the library's store-only kernel
+    over a buffer far beyond the caches: one sweep over the whole buffer, and one wavefront per
+    contiguous region of about one observation (the pattern of the observation stores; with
+    non-temporal stores in workgroup order, as a step launch issues them, and with ordinary stores
+    and consecutive regions on the same die, as a rollout does)."""
+    dev = torch.device("cuda", 0)
+    buf = torch.empty(total, dtype=torch.uint8, device=dev)
+    out = {}
+    region = max(16, (region_bytes + 15) // 16 * 16)
+    for key, rb, order, mode in (("linear_fill", 64 << 10, 1, 2),
+                                 ("region_stores_step", region, 0, 2),
+                                 ("region_stores_rollout", region, 2, 1)):
+        n = total // rb
+        binding.pcgrl_store_rate(buf, n, rb, mode, order)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(3):
+            binding.pcgrl_store_rate(buf, n, rb, mode, order)
+        b.record()
+        torch.cuda.synchronize()
+        out[key] = n * rb * 3 / (a.elapsed_time(b) * 1e-3) / 1e9
+    out["region_bytes"] = region
+    out["unit"] = "GB/s"
+    out["bytes"] = total
+    del buf
+    return out
+
+
+def summarise(run: GpuRun, step, roll):
+    """Per-step and rollout figures of one workload with the roofline they are held against."""
+    cfg, B = run.cfg, run.B
+    abytes = algorithmic_bytes_per_env_step(cfg)
+    launch_s = step["event_ms_per_step"] * 1e-3
+    achieved = abytes * B / launch_s / 1e9
+    traffic = profile_table("hbm_traffic.txt", run.tag)
+    valu = profile_table("valu_per_launch.txt", run.tag)      # wave-level vector instructions per launch
+    valu_frac = valu / launch_s / 1e9 / VALU_PEAK_GINST if valu else None
+    hbm_frac = achieved / HBM_PEAK_GBS
+    # which ceiling is nearer: the launch itself (an empty launch is 1.5 us), the vector ALUs, or HBM
+    if launch_s < 3.0e-6 and hbm_frac < 0.1:
+        bound = "launch"
+    elif valu_frac is not None and valu_frac > hbm_frac:
+        bound = "alu"
+    else:
+        bound = "hbm"
+    out = {
+        "value": B / (step["wall_ms_per_step"] * 1e-3), "us_per_step": step["wall_ms_per_step"] * 1e3,
+        "kernel_us_per_step": launch_s * 1e6, "bound": bound, "frac": hbm_frac,
+        "achieved_GBs": achieved, "algorithmic_bytes_per_env_step": abytes,
+        "obs_slots": step["obs_slots"], "timed_steps": step["timed_steps"],
+    }
+    if traffic:
+        out["traffic"] = traffic
+        out["frac_traffic"] = traffic / launch_s / 1e9 / HBM_PEAK_GBS
+    if valu_frac is not None:
+        out["valu_wave_insts_per_launch"] = valu
+        out["valu_issue_frac"] = valu_frac
+    if roll is not None:
+        rbytes = rollout_bytes_per_env_step(cfg)
+        rs = roll["event_s_per_step"]
+        out["rollout"] = {
+            "value": B / roll["wall_s_per_step"], "us_per_step": roll["wall_s_per_step"] * 1e6,
+            "frac": rbytes * B / rs / 1e9 / HBM_PEAK_GBS, "achieved_GBs": rbytes * B / rs / 1e9,
+            "algorithmic_bytes_per_env_step": rbytes, "steps_per_launch": roll["steps_per_launch"],
+            "launches": roll["launches"], "obs_slots": roll["obs_slots"],
+        }
+    return out
 
 
 def main():
@@ -101,19 +342,26 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="maze16")
+    ap.add_argument("--workload", default="maze64")
     ap.add_argument("--batch", type=int, default=None)
-    ap.add_argument("--reps", type=int, default=3, help="timed repetitions of the K steps; the median is reported")
+    ap.add_argument("--reps", type=int, default=3, help="timed repetitions; the median is reported")
     ap.add_argument("--regions", choices=["incremental", "recount"], default="incremental")
     ap.add_argument("--max-changes", type=int, default=None, metavar="N",
                     help="end an episode after N modifying edits as well (episodes then end, and "
                          "levels restart, at different steps; default: the workload's own setting)")
     ap.add_argument("--obs-store", choices=["auto", "cached", "stream", "through"], default="auto",
                     help="how observations are stored (default: the library's own rule)")
+    ap.add_argument("--obs-ring", choices=["ring", "one"], default="ring",
+                    help="per-step launches write a ring of observation buffers four times the "
+                         "memory-side cache (default: every byte reaches HBM) or rewrite one buffer")
+    ap.add_argument("--obs-pitch", choices=["dense", "lines"], default="lines",
+                    help="observation layout: one level's observation directly after the other, or "
+                         "every level's observation padded to whole 128-byte lines (obs_pitch; default)")
     ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
                     help="replay a HIP graph of pcgrl_step launches (default) or call it from Python")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--no-rollout", action="store_true", help="skip the pcgrl_rollout leg")
+    ap.add_argument("--no-table", action="store_true", help="skip the per-workload table and the store rates")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run 20 plain device copies of MIB MiB (the known "
                          "traffic that scales rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
@@ -127,6 +375,7 @@ def main():
     import torch
     from paper_2408_12525_amd import binding, workloads as wl
 
+    torch.cuda.set_device(0)
     if args.copy_calibration:
         n = args.copy_calibration << 20
         src = torch.full((n,), 7, dtype=torch.uint8, device="cuda")
@@ -137,132 +386,71 @@ def main():
         print(json.dumps({"copy_calibration_bytes": n, "copies": 20}))
         return
 
-    cfg = wl.workload(args.workload, batch=args.batch)
-    cfg["regions_mode"] = wl.REGIONS_RECOUNT if args.regions == "recount" else wl.REGIONS_INCREMENTAL
-    cfg["obs_store_mode"] = ["auto", "cached", "stream", "through"].index(args.obs_store)
-    if args.max_changes is not None:
-        cfg["max_changes"] = args.max_changes
-    K = args.steps if args.steps is not None else cfg["max_steps"]
     W = args.warmup
-    B = cfg["batch"]
-    dev = torch.device("cuda", 0)
-    torch.cuda.set_device(dev)
+    head = GpuRun(args.workload, args.batch, args)
+    cfg, B = head.cfg, head.B
+    K = args.steps if args.steps is not None else cfg["max_steps"]
+    step = head.per_step(K, W, args.reps)
+    roll = None if args.no_rollout else head.rollout(max(K, 100))
+    hs = summarise(head, step, roll)
+    head.close()
 
-    env = binding.Pcgrl(cfg, 0)
-    obs = env.new_obs()
-    rew = torch.empty(B, dtype=torch.float32, device=dev)
-    done = torch.empty(B, dtype=torch.uint8, device=dev)
-    seed, aseed = 0, 1
-    n_act = min(K, 1000)   # the action stream repeats after 1000 steps (keeps it small in HBM)
-    acts = torch.from_numpy(wl.random_actions(cfg, aseed, n_act)).to(dev)
-    warm = torch.from_numpy(wl.random_actions(cfg, aseed + 1, max(W, 1))).to(dev)
-
-    # One HIP graph holds `chunk` consecutive pcgrl_step launches (each a kernel node with its own
-    # slice of the action stream); replaying it is how a launch-bound loop is meant to be driven
-    # on this hardware.  --launch eager calls pcgrl_step from Python instead (about 9 us of host
-    # time per call, which then bounds small batches).
-    chunk = min(n_act, K)
-    while K % chunk:
-        chunk -= 1
-    graph = None
-    if args.launch == "graph":
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.stream(side):
-            env.pcgrl_reset(seed, obs)
-            with torch.cuda.graph(graph, stream=side):
-                for t in range(chunk):
-                    env.pcgrl_step(acts[t], obs, rew, done)
-        torch.cuda.current_stream().wait_stream(side)
-        torch.cuda.synchronize()
-
-    times_ms, ev_ms = [], []
-    for rep in range(args.reps):
-        env.pcgrl_reset(seed, obs)
-        for t in range(W):
-            env.pcgrl_step(warm[t], obs, rew, done)
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        e0.record()                      # on the current stream, the one the steps run on
-        if graph is not None:
-            for _ in range(K // chunk):
-                graph.replay()
-        else:
-            for t in range(K):
-                env.pcgrl_step(acts[t % n_act], obs, rew, done)
-        e1.record()
-        torch.cuda.synchronize()
-        times_ms.append((time.perf_counter() - t0) * 1e3)
-        ev_ms.append(e0.elapsed_time(e1))
-    order = sorted(range(args.reps), key=lambda i: times_ms[i])
-    mid = order[len(order) // 2]
-    wall_ms, kern_ms = times_ms[mid], ev_ms[mid]
-    ms_per_step = wall_ms / K
-    value = B * K / (wall_ms * 1e-3)
-
-    abytes = algorithmic_bytes_per_env_step(cfg)
-    per_launch = abytes * B
-    launch_s = kern_ms * 1e-3 / K        # average launch-to-launch time on the stream (HIP events)
-    achieved = per_launch / launch_s / 1e9
-    tag = f"{args.workload}_B{B}"
+    attain = None
+    if not args.no_table:
+        attain = store_rates(torch, binding, head.obs_env_bytes)
+    ms_per_step = step["wall_ms_per_step"]
     out = {
         "metric": "env-steps/sec (edit+metrics+reward+obs) at 1 GPU; % of HBM roofline",
-        "value": value, "unit": "env-steps/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "value": hs["value"], "unit": "env-steps/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "u8", "data": "synthetic",
-        "config": {"workload": tag, "problem": ["binary", "maze", "dungeon"][cfg["problem"]],
+        "config": {"workload": head.tag, "problem": ["binary", "maze", "dungeon"][cfg["problem"]],
                    "batch": B, "map": f"{cfg['max_h']}x{cfg['max_w']}",
                    "min_map": f"{cfg['min_h']}x{cfg['min_w']}", "obs_w": cfg["obs_w"],
-                   "obs_bytes_per_env": wl.obs_bytes(cfg), "n_frozen": cfg["n_frozen"],
-                   "regions": args.regions, "max_changes": cfg.get("max_changes", 0), "obs_store": args.obs_store, "launch": args.launch, "launches_per_step": 1, "reps": args.reps,
-                   "algorithmic_bytes_per_env_step": abytes},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_from_profiles(tag),
-                     "kernel": "step_kernel", "avg_launch_us": launch_s * 1e6},
+                   "obs_bytes_per_env": head.obs_env_bytes, "obs_pitch_bytes": head.obs_stride,
+                   "n_frozen": cfg["n_frozen"],
+                   "regions": args.regions, "max_changes": cfg.get("max_changes", 0),
+                   "obs_store": args.obs_store, "launch": args.launch, "launches_per_step": 1,
+                   "reps": args.reps, "timed_steps_per_rep": step["timed_steps"],
+                   "obs_slots": step["obs_slots"],
+                   "algorithmic_bytes_per_env_step": hs["algorithmic_bytes_per_env_step"]},
+        "roofline": {"bound": hs["bound"], "achieved": hs["achieved_GBs"], "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": hs["frac"], "traffic": hs.get("traffic"),
+                     "frac_traffic": hs.get("frac_traffic"), "kernel": "step_kernel",
+                     "avg_launch_us": hs["kernel_us_per_step"]},
     }
-    # The same K steps driven through pcgrl_rollout: T steps per launch, levels resident in
-    # registers in between, every step still writes its observation, reward and done flag.  The
-    # observations go into a slot per step (what a learner that keeps the whole rollout needs;
-    # fewer slots only where T of them would exceed 16 GiB), so that every byte written has to
-    # reach HBM: one slot rewritten T times would largely be absorbed by the caches.  Reported
-    # beside the headline, never instead of it.
-    if not args.no_rollout:
-        T = min(chunk, 100)
-        launches = max(1, K // T)
-        racts = acts[:T].contiguous()
-        slots = max(1, min(T, (16 << 30) // max(1, obs.numel())))
-        robs = torch.empty((slots,) + tuple(obs.shape), dtype=torch.uint8, device=dev)
-        rrew = torch.empty((T, B), dtype=torch.float32, device=dev)
-        rdone = torch.empty((T, B), dtype=torch.uint8, device=dev)
-        env.pcgrl_reset(seed, obs)
-        env.pcgrl_rollout(racts, robs, rrew, rdone)
-        r0 = torch.cuda.Event(enable_timing=True)
-        r1 = torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        r0.record()
-        for _ in range(launches):
-            env.pcgrl_rollout(racts, robs, rrew, rdone)
-        r1.record()
-        torch.cuda.synchronize()
-        rwall = time.perf_counter() - t0
-        rbytes = wl.obs_bytes(cfg) + 4 + 4 + 1          # per env-step: obs + action + reward + done
-        rlaunch_s = r0.elapsed_time(r1) * 1e-3 / launches
-        out["rollout"] = {
-            "value": B * T * launches / rwall, "unit": "env-steps/s", "steps_per_launch": T,
-            "launches": launches, "obs_slots": slots, "us_per_step": rwall / (T * launches) * 1e6,
-            "algorithmic_bytes_per_env_step": rbytes,
-            "roofline": {"bound": "hbm", "achieved": rbytes * B * T / rlaunch_s / 1e9,
-                         "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": rbytes * B * T / rlaunch_s / 1e9 / HBM_PEAK_GBS,
-                         "kernel": "step_kernel<..., rollout>", "avg_launch_us": rlaunch_s * 1e6},
-        }
-    env.close()
+    if attain:
+        out["roofline"]["attainable"] = attain
+        out["roofline"]["frac_attainable"] = hs["achieved_GBs"] / attain["region_stores_step"]
+    if "valu_issue_frac" in hs:
+        out["roofline"]["valu_issue_frac"] = hs["valu_issue_frac"]
+    if "rollout" in hs:
+        r = hs["rollout"]
+        out["rollout"] = dict(r, unit="env-steps/s",
+                              roofline={"bound": "hbm", "achieved": r["achieved_GBs"], "peak": HBM_PEAK_GBS,
+                                        "unit": "GB/s", "frac": r["frac"],
+                                        "kernel": "step_kernel<..., rollout>"})
+        if attain:
+            out["rollout"]["roofline"]["frac_attainable"] = r["achieved_GBs"] / attain["region_stores_rollout"]
+
+    # every other workload, shorter (300 steps per repetition, one repetition of >= 5 ms), and the
+    # 16x16 binary problem at the batch the steps-per-second target is read at
+    if not args.no_table:
+        table = {head.tag: {k: v for k, v in hs.items()}}
+        todo = [(n, None) for n in wl.WORKLOADS] + [("binary16", 262144)]
+        for name, batch in todo:
+            run = GpuRun(name, batch, args)
+            if run.tag in table:
+                run.close()
+                continue
+            Kt = min(300, run.cfg["max_steps"])
+            s = run.per_step(Kt, W, 1)
+            r = None if args.no_rollout else run.rollout(Kt)
+            table[run.tag] = summarise(run, s, r)
+            run.close()
+        out["configs"] = table
     if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(cfg, seed, aseed)
+        out["cpu_baseline"] = cpu_baseline(cfg, 0, 1)
     print(json.dumps(out))
 
 

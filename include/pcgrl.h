@@ -130,7 +130,17 @@ typedef struct {
                            writes: 0 = automatic; 1, 2 or 4, at most what the metrics wavefront
                            holds (levels_per_wave); each workgroup then has that many more
                            observation wavefronts */
+  int32_t obs_pitch;    /* layout of every `obs` argument: 0 = dense, one level's observation
+                           directly after the other; > 0 = bytes from one level's observation to the
+                           next (a multiple of 16, not less than the observation itself);
+                           PCGRL_OBS_PITCH_LINES = the observation's size rounded up to a multiple
+                           of 128 bytes, so that no two levels share a cache line (stores whose
+                           lines are written by one wavefront only reach memory about half as fast
+                           again).  The bytes between two observations are written as zeros.  The
+                           caller sees [batch][pitch] bytes, e.g. as a strided [batch][C][ow][ow] view */
 } pcgrl_config;
+
+#define PCGRL_OBS_PITCH_LINES (-1)
 
 /* Fills *cfg with this library's defaults for a problem: fixed 16x16 map, window 31, border
  * padding, scan order, no pinpoints, no controlled metric, 1000 steps, autoreset, uniform initial
@@ -226,11 +236,31 @@ int pcgrl_get_targets(pcgrl_ctx* ctx, int32_t* out, void* stream);
 /* Shape queries (host side, no GPU work).  out: host pointer to 4 ints = batch, C, obs_w, obs_w. */
 int pcgrl_obs_shape(const pcgrl_ctx* ctx, int32_t out[4]);
 int64_t pcgrl_obs_bytes(const pcgrl_ctx* ctx); /* bytes of one level's observation in obs_format */
+int64_t pcgrl_obs_stride(const pcgrl_ctx* ctx); /* bytes from one level's observation to the next
+                                                    (pcgrl_obs_bytes, or the pitch obs_pitch asks for);
+                                                    an `obs` argument holds batch times this many bytes */
 int pcgrl_num_metrics(const pcgrl_ctx* ctx);
 int pcgrl_num_tiles(const pcgrl_ctx* ctx);
 
 /* Number of out-of-range actions seen since creation.  Waits for `stream`.  out: host pointer. */
 int pcgrl_bad_action_count(pcgrl_ctx* ctx, uint64_t* out, void* stream);
+
+/* Measurement aid (no passage of the paper: it is the yardstick its store-bound steps are held
+ * against).  One launch that does nothing but write n_regions * region_bytes bytes to dst with
+ * aligned 16-byte stores of the kind `store_mode` names (PCGRL_OBS_STORE_CACHED / _STREAM /
+ * _THROUGH).  order: PCGRL_STORE_ORDER_REGIONS = one wavefront per contiguous region of
+ * region_bytes, workgroup b takes region b -- the pattern of the observation writer of a step;
+ * _REGIONS_BY_DIE = the same with consecutive regions on the same accelerator die, as a rollout
+ * deals them; _LINEAR = one sweep in which consecutive wavefronts write consecutive 1 KiB pieces.
+ * dst: device pointer on the current device (there is no context), 16-byte aligned, at least
+ * n_regions * region_bytes bytes; its contents afterwards are unspecified.
+ * Errors: E_NULL; E_CONFIG if n_regions < 1, region_bytes is not a positive multiple of 16 (of
+ * 1024 for the linear order), dst is misaligned, or store_mode / order is out of range. */
+#define PCGRL_STORE_ORDER_REGIONS 0
+#define PCGRL_STORE_ORDER_LINEAR 1
+#define PCGRL_STORE_ORDER_REGIONS_BY_DIE 2
+int pcgrl_store_rate(uint8_t* dst, int64_t n_regions, int32_t region_bytes, int32_t store_mode,
+                     int32_t order, void* stream);
 
 /* Checks on the GPU that the cross-lane row exchange used by the flood kernels moves data the way
  * the kernels assume (each of the 3 lane groupings, both directions).  Synchronises.

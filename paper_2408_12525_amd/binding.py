@@ -37,6 +37,7 @@ class PcgrlConfig(C.Structure):
         ("ctrl_hi", C.c_int32 * MAX_METRICS),
         ("obs_frozen_channel", C.c_int32),
         ("split_obs_levels", C.c_int32),
+        ("obs_pitch", C.c_int32),
     ]
 
 
@@ -44,8 +45,8 @@ EXPORTS = [
     "pcgrl_config_default", "pcgrl_create", "pcgrl_destroy", "pcgrl_reset", "pcgrl_step", "pcgrl_rollout",
     "pcgrl_metrics", "pcgrl_exact_diameter", "pcgrl_observe", "pcgrl_get_state", "pcgrl_set_state", "pcgrl_set_targets",
     "pcgrl_get_targets",
-    "pcgrl_obs_shape", "pcgrl_obs_bytes", "pcgrl_num_metrics", "pcgrl_num_tiles", "pcgrl_bad_action_count",
-    "pcgrl_selftest", "pcgrl_strerror",
+    "pcgrl_obs_shape", "pcgrl_obs_bytes", "pcgrl_obs_stride", "pcgrl_num_metrics", "pcgrl_num_tiles", "pcgrl_bad_action_count",
+    "pcgrl_selftest", "pcgrl_store_rate", "pcgrl_strerror",
 ]
 
 _lib = None
@@ -90,10 +91,13 @@ def load():
     L.pcgrl_obs_shape.argtypes = [p, C.POINTER(i32 * 4)]
     L.pcgrl_obs_bytes.argtypes = [p]
     L.pcgrl_obs_bytes.restype = C.c_int64
+    L.pcgrl_obs_stride.argtypes = [p]
+    L.pcgrl_obs_stride.restype = C.c_int64
     L.pcgrl_num_metrics.argtypes = [p]
     L.pcgrl_num_tiles.argtypes = [p]
     L.pcgrl_bad_action_count.argtypes = [p, C.POINTER(u64), p]
     L.pcgrl_selftest.argtypes = [C.c_int, C.POINTER(i32)]
+    L.pcgrl_store_rate.argtypes = [p, C.c_int64, i32, i32, i32, p]
     L.pcgrl_strerror.argtypes = [C.c_int]
     L.pcgrl_strerror.restype = C.c_char_p
     _lib = L
@@ -129,6 +133,16 @@ def pcgrl_selftest(device: int = 0) -> int:
     return n.value
 
 
+def pcgrl_store_rate(dst, n_regions: int, region_bytes: int, store_mode: int = 1, order: int = 0):
+    """One store-only launch over dst (uint8 tensor on the current device); see pcgrl_store_rate."""
+    if not (isinstance(dst, torch.Tensor) and dst.is_cuda and dst.dtype == torch.uint8 and dst.is_contiguous()):
+        raise PcgrlError("dst must be a contiguous uint8 tensor on the GPU")
+    if dst.numel() < n_regions * region_bytes:
+        raise PcgrlError("dst is smaller than n_regions * region_bytes")
+    _check(load().pcgrl_store_rate(C.c_void_p(dst.data_ptr()), n_regions, region_bytes, store_mode,
+                                   int(order), C.c_void_p(_stream_ptr(dst.device))), "pcgrl_store_rate")
+
+
 def _stream_ptr(device) -> int:
     return torch.cuda.current_stream(device).cuda_stream
 
@@ -145,8 +159,12 @@ class Pcgrl:
         shp = (C.c_int32 * 4)()
         _check(self.L.pcgrl_obs_shape(self.h, C.byref(shp)), "pcgrl_obs_shape")
         self.obs_shape = tuple(shp)
-        if self.cfg.obs_format != 0:     # bit-packed: one flat byte row per level
-            self.obs_shape = (shp[0], int(self.L.pcgrl_obs_bytes(self.h)))
+        self.obs_bytes = int(self.L.pcgrl_obs_bytes(self.h))
+        self.obs_stride = int(self.L.pcgrl_obs_stride(self.h))
+        self.onehot_shape = tuple(shp)
+        if self.cfg.obs_format != 0 or self.obs_stride != self.obs_bytes:
+            # bit-packed or pitched: one flat byte row per level
+            self.obs_shape = (shp[0], self.obs_stride)
         self.B = self.cfg.batch
         self.M = self.L.pcgrl_num_metrics(self.h)
         self.K = self.L.pcgrl_num_tiles(self.h)
@@ -178,6 +196,21 @@ class Pcgrl:
 
     def new_obs(self):
         return torch.empty(self.obs_shape, dtype=torch.uint8, device=self.device)
+
+    def obs_view(self, obs):
+        """The observations proper inside an `obs` buffer (leading slot dimensions allowed): the
+        [..., batch, C, ow, ow] one-hot cells as a strided view, or the [..., batch, bytes] packed
+        rows, without the bytes a pitch adds after each level."""
+        if self.obs_stride == self.obs_bytes and self.cfg.obs_format == 0:
+            return obs
+        rows = obs[..., :self.obs_bytes]
+        if self.cfg.obs_format != 0:
+            return rows
+        lead = tuple(obs.shape[:-2])
+        strides = tuple(obs.stride()[:-2])
+        _, Cc, ow, _ = self.onehot_shape
+        return rows.as_strided(lead + (self.B, Cc, ow, ow), strides + (self.obs_stride, ow * ow, ow, 1),
+                               obs.storage_offset())
 
     def _st(self):
         return C.c_void_p(_stream_ptr(self.device))

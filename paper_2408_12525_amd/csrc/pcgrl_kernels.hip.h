@@ -64,7 +64,7 @@ struct KArgs {
   uint64_t seed;
   int32_t max_h, max_w, min_h, min_w;
   int32_t obs_w, pad_mode, pos_mode, n_frozen, max_steps, max_changes, autoreset, regions_mode;
-  int32_t env_obs_bytes;  // bytes of one level's observation: C * obs_w * obs_w, or an eighth (rounded up) when packed
+  int32_t env_obs_bytes;  // bytes from one level's observation to the next: C * obs_w * obs_w, or an eighth (rounded up) when packed, or the configured pitch
   int32_t obs_packed;     // non-zero: bit-packed observation format
   int32_t obs_frozen_channel;  // non-zero: a last channel marks the pinpoint cells in view
   int32_t stream_obs;     // how observations are stored: kStoreCached / kStoreStream / kStoreThrough
@@ -889,7 +889,9 @@ __device__ __forceinline__ void write_obs(const KArgs& a, const Lanes<S>& L, con
     for (int q = pl.q_lo + L.lane; q < pl.q_hi; q += 64) {
       const uint4 v = widen(lds16[q]);
       u32x4 nv = {v.x, v.y, v.z, v.w};
-      asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(pl.base + ((uint32_t)q << 4)), "v"(nv));
+      // (the s_nop: a store of more than 64 bits needs one wait state before a vector instruction
+      // may overwrite its data registers, and the compiler does not look inside the asm string)
+      asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 0" ::"v"(pl.base + ((uint32_t)q << 4)), "v"(nv));
     }
   } else if (a.stream_obs == kStoreStream) {
     // far more than the last-level cache holds: stream the bytes past it
@@ -1687,6 +1689,35 @@ __global__ void get_targets_kernel(const uint32_t* src, int32_t* dst, int B, int
   uint32_t t = src[(size_t)(idx / M) * kMaxMetrics + idx % M];
   dst[2 * idx] = (int32_t)(t & 0xffffu);
   dst[2 * idx + 1] = (int32_t)(t >> 16);
+}
+
+// Measurement aid: nothing but stores, in the pattern of the observation writer (one wavefront per
+// contiguous region, aligned 16-byte stores, 1 KiB per wavefront instruction; with by_die the
+// regions are dealt to the workgroups the way a rollout deals its level groups, see
+// level_group_of_block) or, with `linear`, as one sweep over the whole buffer (wavefront w writes
+// the 1 KiB pieces w, w + n, w + 2n, ...).  What it sustains is the store rate that the step
+// kernels can be held against.
+__global__ __launch_bounds__(64) void store_rate_kernel(uint8_t* dst, int64_t n_regions, int32_t region_bytes,
+                                                        int32_t mode, int32_t linear, int32_t by_die) {
+  const int lane = (int)(threadIdx.x & 63u);
+  const int64_t w = level_group_of_block<true>(by_die), n = gridDim.x;
+  const int chunks = region_bytes >> 4;  // 16-byte chunks per region
+  const u32x4 v = {0x01010101u, 0x00010001u, 0x01000100u, (uint32_t)w};
+  for (int64_t r = w; r < n_regions; r += n) {
+    for (int q = lane; q < chunks; q += 64) {
+      const int64_t piece = q >> 6;  // which 1 KiB piece of the region
+      const int64_t off = linear ? ((piece * n_regions + r) << 10) + ((int64_t)(q & 63) << 4)
+                                 : r * (int64_t)region_bytes + ((int64_t)q << 4);
+      u32x4* at = reinterpret_cast<u32x4*>(dst + off);
+      if (mode == kStoreThrough) {
+        asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 0" ::"v"(at), "v"(v) : "memory");
+      } else if (mode == kStoreStream) {
+        __builtin_nontemporal_store(v, at);
+      } else {
+        *at = v;
+      }
+    }
+  }
 }
 
 // Cross-lane exchange check: the DPP shifts against the plain shuffle definition.

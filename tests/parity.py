@@ -24,6 +24,16 @@ def expected_obs(cfg, onehot):
     return onehot
 
 
+def check_obs(gpu, obs, want, ctx, sl=slice(None)):
+    """Compares the observations inside a GPU buffer with the oracle's, in the context's format
+    (bit-packed or not); with a pitched layout the bytes between two levels must be zero."""
+    cfgd = {"obs_format": gpu.cfg.obs_format}
+    assert_same("obs", gpu.obs_view(obs)[sl], expected_obs(cfgd, want)[sl], ctx)
+    if gpu.obs_stride != gpu.obs_bytes:
+        pad = obs[..., gpu.obs_bytes:]
+        assert int(pad.count_nonzero()) == 0, f"bytes between two levels' observations are not zero {ctx}"
+
+
 def run_parity(cfg, steps, seed=1, aseed=2, bad_fraction=0.0, check_every=1, state_every=25,
                env_slice=None, targets=None, label=""):
     """Steps both implementations `steps` times.  Observations, rewards, done flags and metrics
@@ -45,7 +55,7 @@ def run_parity(cfg, steps, seed=1, aseed=2, bad_fraction=0.0, check_every=1, sta
     if targets is not None:
         gpu.pcgrl_set_targets(torch.from_numpy(targets).to(dev))
         cpu.set_targets(targets)
-    assert_same("obs", obs[sl], expected_obs(cfg, want_obs)[sl], "after reset")
+    check_obs(gpu, obs, want_obs, "after reset", sl)
     assert_same("metrics", gpu.pcgrl_metrics()[sl], cpu.metrics()[sl], "after reset")
     compare_state(gpu, cpu, "after reset")
     acts = wl.random_actions(cfg, aseed, steps, bad_fraction)
@@ -62,7 +72,7 @@ def run_parity(cfg, steps, seed=1, aseed=2, bad_fraction=0.0, check_every=1, sta
             bad = np.flatnonzero(~(g[sl] == r[sl]))
             assert len(bad) == 0, (f"reward differs {ctx} in {len(bad)} envs; first env {bad[0]}: "
                                    f"gpu={g[sl][bad[0]]} oracle={r[sl][bad[0]]}")
-            assert_same("obs", obs[sl], expected_obs(cfg, o)[sl], ctx)
+            check_obs(gpu, obs, o, ctx, sl)
         if t % state_every == 0 or t == steps - 1:
             compare_state(gpu, cpu, f"at step {t}")
     if bad_fraction > 0:

@@ -5,7 +5,7 @@ import torch
 
 import levels
 import oracle
-from parity import assert_same, compare_state, expected_obs, run_parity
+from parity import assert_same, check_obs, compare_state, expected_obs, run_parity
 from paper_2408_12525_amd import binding, workloads as wl
 
 pytestmark = pytest.mark.gpu
@@ -13,6 +13,27 @@ pytestmark = pytest.mark.gpu
 
 def test_lane_exchange_selftest():
     assert binding.pcgrl_selftest(0) == 0
+
+
+@pytest.mark.parametrize("mode", [1, 2, 3], ids=["cached", "non-temporal", "write-through"])
+def test_store_rate_kernel_writes_every_byte_it_is_asked_to(mode):
+    """The store-only measurement kernel: every 16-byte piece of the regions is written (first
+    word 0x01010101), nothing after them is touched; regions pattern and linear sweep."""
+    dev = torch.device("cuda", 0)
+    for n_regions, region, order in ((37, 4816, 0), (5, 16, 0), (70000, 1936, 0), (9, 3072, 1), (37, 4816, 2),
+                                     (70001, 1936, 2)):
+        buf = torch.full((n_regions * region + 64,), 0xEE, dtype=torch.uint8, device=dev)
+        binding.pcgrl_store_rate(buf, n_regions, region, mode, order)
+        torch.cuda.synchronize()
+        words = buf[:n_regions * region].view(torch.int32).view(-1, 4)
+        assert bool((words[:, 0] == 0x01010101).all()), (n_regions, region, order)
+        assert bool((buf[n_regions * region:] == 0xEE).all())
+    with pytest.raises(binding.PcgrlError):
+        binding.pcgrl_store_rate(buf, 4, 24, mode, 0)          # not a multiple of 16
+    with pytest.raises(binding.PcgrlError):
+        binding.pcgrl_store_rate(buf, 4, 2048 + 16, mode, 1)   # the linear order wants whole KiB pieces
+    with pytest.raises(binding.PcgrlError):
+        binding.pcgrl_store_rate(buf, 4, 1024, mode, 3)        # no such order
 
 
 SMALL = [
@@ -56,20 +77,29 @@ SMALL = [
 ]
 
 
-@pytest.mark.parametrize("lpw,split,olv", [(0, 0, 0), (2, 1, 0), (4, 2, 0), (1, 1, 0), (4, 2, 2), (4, 2, 1), (2, 2, 1)],
-                         ids=["auto", "lpw2-unsplit", "lpw4-split", "lpw1-unsplit", "lpw4-split-obs2",
-                              "lpw4-split-obs1", "lpw2-split-obs1"])
-@pytest.mark.parametrize("label,cfg,steps,extra", SMALL, ids=[s[0] for s in SMALL])
+SHAPES = [(0, 0, 0, "auto"), (2, 1, 0, "lpw2-unsplit"), (4, 2, 0, "lpw4-split"), (1, 1, 0, "lpw1-unsplit"),
+          (4, 2, 2, "lpw4-split-obs2"), (4, 2, 1, "lpw4-split-obs1"), (2, 2, 1, "lpw2-split-obs1")]
+
+
+def _applies(cfg, lpw, olv):
+    """A 64-row level fills the wavefront (no packing to choose), and for 32-row levels a request
+    for four levels per wavefront is the same launch shape as one for two."""
+    side = max(cfg["max_h"], cfg["max_w"])
+    return not (lpw > 1 and side > 32) and not (olv and lpw > 2 and side > 16)
+
+
+SMALL_CASES = [pytest.param(label, cfg, steps, extra, lpw, split, olv, id=f"{label}-{sid}")
+               for (label, cfg, steps, extra) in SMALL for (lpw, split, olv, sid) in SHAPES
+               if _applies(cfg, lpw, olv)]
+
+
+@pytest.mark.parametrize("label,cfg,steps,extra,lpw,split,olv", SMALL_CASES)
 def test_small_configs_every_step(label, cfg, steps, extra, lpw, split, olv):
     """lpw = levels packed into one wavefront (automatic = 1 at these batch sizes, 2, as many as
     the size class takes); split = one wavefront per level group, or a metrics wavefront and
     observation wavefronts (automatic = split at these batch sizes); olv = levels per observation
-    wavefront of a split step (0 = as many as the metrics wavefront holds)."""
-    side = max(cfg["max_h"], cfg["max_w"])
-    if lpw > 1 and side > 32:
-        pytest.skip("a 64-row level fills the wavefront")
-    if olv and lpw > 2 and side > 16:
-        pytest.skip("the same shape as lpw2-split-obs1 in this size class")
+    wavefront of a split step (0 = as many as the metrics wavefront holds).  Only the launch shapes
+    that exist for a configuration's size class are listed."""
     run_parity(dict(cfg, levels_per_wave=lpw, split_step=split, split_obs_levels=olv), steps,
                label=f"{label} lpw={lpw} split={split} obs levels={olv}", **extra)
 
@@ -95,6 +125,60 @@ def test_every_way_of_storing_the_observation(name, batch, split, mode):
     for k, o in want.items():
         assert_same("obs", obs[k], o, f"rollout slot {k}, store mode {mode}")
     gpu.close()
+
+
+PITCHED = [
+    ("maze16 lines", wl.workload("maze16", batch=70, max_steps=30, obs_pitch=-1), 4864),
+    ("binary16 lines", wl.workload("binary16", batch=67, max_steps=30, obs_pitch=-1), 2048),
+    ("binary32 ow3, 16-byte pitch", wl.workload("binary32_rand_ow3", batch=41, max_steps=30, obs_pitch=32), 32),
+    ("binary32 ow63 lines", wl.workload("binary32_rand_ow63", batch=9, max_steps=30, obs_pitch=-1), 12032),
+    ("dungeon32 lines", wl.workload("dungeon32", batch=21, max_steps=30, obs_pitch=-1), 1920),
+    ("maze64 lines", wl.workload("maze64", batch=5, max_steps=30, obs_pitch=-1), 4864),
+    ("maze64 wide pitch", wl.workload("maze64", batch=3, max_steps=30, obs_pitch=4805 // 16 * 16 + 48), 4848),
+    ("maze16 bit-packed lines", wl.workload("maze16", batch=33, max_steps=30, obs_format=1, obs_pitch=-1), 640),
+    ("dungeon64 ow5 bit-packed, pitch 32", wl.make_config(wl.DUNGEON, 7, 64, 5, min_size=20, max_steps=30, obs_format=1,
+                                                           obs_pitch=32), 32),
+    ("exact multiple of a line stays dense", wl.make_config(wl.BINARY, 10, 16, 8, max_steps=20, pad_mode=wl.PAD_WALL,
+                                                             obs_pitch=-1), 128),
+]
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2, 3], ids=["auto", "cached", "non-temporal", "write-through"])
+@pytest.mark.parametrize("split", [1, 2], ids=["unsplit", "split"])
+@pytest.mark.parametrize("label,cfg,stride", PITCHED, ids=[c[0] for c in PITCHED])
+def test_pitched_observation_layout(label, cfg, stride, split, mode):
+    """obs_pitch: every level's observation starts a fixed number of bytes after the one before
+    (here mostly a whole number of 128-byte lines); the observation itself is unchanged and the
+    bytes in between are zeros.  Steps, reset and observe in both launch shapes and every store
+    kind, then a rollout into a ring of such buffers, all against the oracle's dense bytes."""
+    cfg = dict(cfg, obs_store_mode=mode, split_step=split)
+    dev = torch.device("cuda", 0)
+    gpu = binding.Pcgrl(cfg, 0)
+    assert gpu.obs_stride == stride
+    if stride != gpu.obs_bytes:
+        assert gpu.obs_shape == (cfg["batch"], stride)
+    gpu.close()
+    run_parity(cfg, 45, label=f"{label} split={split} store={mode}")
+    gpu, cpu = binding.Pcgrl(cfg, 0), oracle.Oracle(cfg)
+    gpu.pcgrl_reset(3)
+    cpu.reset(3)
+    check_obs(gpu, gpu.pcgrl_observe(), cpu.observe(), "pcgrl_observe")
+    T = 37
+    acts_np = wl.random_actions(cfg, 5, T)
+    obs = torch.full((3,) + gpu.obs_shape, 0xAB, dtype=torch.uint8, device=dev)
+    gpu.pcgrl_rollout(torch.from_numpy(acts_np).to(dev), obs)
+    want = {}
+    for t in range(T):
+        want[t % 3] = cpu.step(acts_np[t])[0]
+    for k, o in want.items():
+        check_obs(gpu, obs[k], o, f"rollout slot {k}")
+    gpu.close()
+
+
+def test_obs_pitch_is_validated():
+    for bad in (-2, 24, 4800, 100):           # unknown code, not a multiple of 16, smaller than the observation
+        with pytest.raises(binding.PcgrlError):
+            binding.Pcgrl(wl.workload("maze16", batch=4, obs_pitch=bad), 0)
 
 
 @pytest.mark.parametrize("name,batch", [("binary16", 300), ("maze16", 130), ("binary32_rand_ow3", 90),
