@@ -359,7 +359,8 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
 
   const size_t rows = (size_t)ctx->B_pad * ctx->S;
   struct { void** p; size_t n; } allocs[] = {
-      {&ctx->d_planes, rows * ctx->word_bytes * ctx->P},
+      // (the binary problem keeps one more plane: the component of the first walkable cell)
+      {&ctx->d_planes, rows * ctx->word_bytes * (ctx->P + (cfg->problem == PCGRL_BINARY ? 1 : 0))},
       {&ctx->d_frozen, rows * ctx->word_bytes},
       {&ctx->d_env, (size_t)ctx->B_pad * sizeof(EnvRec)},
       {&ctx->d_metrics, (size_t)ctx->B_pad * kMaxMetrics * sizeof(int32_t)},

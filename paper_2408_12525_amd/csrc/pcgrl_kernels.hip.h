@@ -276,13 +276,14 @@ constexpr int kShortTrips = 2;
 
 // One sweep of the two-sweep diameter estimate: breadth-first layers from `seed` inside `pass`.
 // Returns the eccentricity of the seed and leaves in `last` the cells of the last layer
-// (the seed itself when nothing else is reachable).  The loop advances two layers per trip and
+// (the seed itself when nothing else is reachable) and in `comp` all the cells reached.  The loop advances two layers per trip and
 // only remembers, per lane, what the last pair of layers that reached the lane added; which of the
 // two layers was the last one is worked out after the loop with one more layer from the cells
 // known before that pair.
 template <int S>
 __device__ __forceinline__ int sweep(const Lanes<S>& L, typename RowWord<S>::T seed,
-                                     typename RowWord<S>::T pass, typename RowWord<S>::T& last) {
+                                     typename RowWord<S>::T pass, typename RowWord<S>::T& last,
+                                     typename RowWord<S>::T& comp) {
   using W = typename RowWord<S>::T;
   W V = seed, added = seed;
   int k = 0, k_last = 0;  // pairs done; the pair that last added cells in this lane
@@ -310,6 +311,7 @@ __device__ __forceinline__ int sweep(const Lanes<S>& L, typename RowWord<S>::T s
   const W second = pair & ~first;
   const bool two = L.gany(second != 0);
   last = two ? second : first;
+  comp = V;  // every cell the sweep reached: the component of the seed
   return kk == 0 ? 0 : 2 * kk - (two ? 0 : 1);
 }
 
@@ -341,14 +343,36 @@ __device__ __forceinline__ int eccentricity(const Lanes<S>& L, typename RowWord<
 
 // Binary domain, footnote: sweep from the first walkable cell x, then from the far end of the
 // longest shortest path out of x (lowest row-major index among equally far cells).
+// `comp` receives the component of x: the estimate depends on nothing else (see
+// diameter_untouched).
 template <int S>
-__device__ __forceinline__ int two_sweep_diameter(const Lanes<S>& L, typename RowWord<S>::T pass) {
+__device__ __forceinline__ int two_sweep_diameter(const Lanes<S>& L, typename RowWord<S>::T pass,
+                                                  typename RowWord<S>::T& comp) {
   using W = typename RowWord<S>::T;
   W x = first_cell<S>(L, pass);
   W far;
-  sweep<S>(L, x, pass, far);
+  sweep<S>(L, x, pass, far, comp);
   W y = first_cell<S>(L, far);
   return eccentricity<S>(L, y, pass);
+}
+
+// Whether an edit leaves the two-sweep estimate as it is.  The estimate is a function of x, the
+// first walkable cell, and of the component of x alone (both sweeps stay inside it, and the far
+// end is chosen among its cells).  An edit that flips the walkability of a cell which neither
+// lies in that component nor touches it leaves the component as it is; x stays the first walkable
+// cell unless the edited cell became walkable and comes before it in row-major order (an x that
+// is walled up lies in the component).  `comp` is the component of x before the edit (empty if no
+// cell was walkable), `cell` the edited cell as a one-cell set in its row's lane, `dcell` its
+// dilation; (py, px) its coordinates.
+template <int S>
+__device__ __forceinline__ bool diameter_untouched(const Lanes<S>& L, typename RowWord<S>::T comp,
+                                                   typename RowWord<S>::T cell, typename RowWord<S>::T dcell,
+                                                   int py, int px, bool now_walkable) {
+  const bool touched = L.gany((dcell & comp) != 0);
+  const uint64_t rows = L.gbits(__builtin_amdgcn_ballot_w64(comp != 0));
+  const int xrow = rows ? ctz(rows) : S;  // row of x (none: every cell comes before it)
+  const bool before = L.gany(cell != 0 && (py < xrow || (py == xrow && px < ctz(comp))));
+  return !touched && !(now_walkable && before);
 }
 
 // Distance from a source set to the nearest cell of a target set, -1 if none is reachable.
@@ -536,9 +560,10 @@ template <int S, int PROBLEM>
 __device__ __forceinline__ void full_metrics(const Lanes<S>& L,
                                              const typename RowWord<S>::T (&p)[Prob<PROBLEM>::P],
                                              typename RowWord<S>::T inside, bool active,
-                                             int (&m)[Prob<PROBLEM>::M]) {
+                                             int (&m)[Prob<PROBLEM>::M], typename RowWord<S>::T& comp) {
   using W = typename RowWord<S>::T;
   using PR = Prob<PROBLEM>;
+  comp = 0;  // binary problem: the component of the first walkable cell (kept with the level)
   W in = active ? inside : (W)0;
   W wall = channel_row<PROBLEM, W>(p, in, 1);
   W pass = in & ~wall;
@@ -546,7 +571,7 @@ __device__ __forceinline__ void full_metrics(const Lanes<S>& L,
   for (int k = 0; k < PR::K; ++k) m[PR::CNT + k] = L.gsum(popc(channel_row<PROBLEM, W>(p, in, k)));
   m[0] = regions_full<S>(L, pass);
   if constexpr (PROBLEM == kBinary) {
-    m[1] = two_sweep_diameter<S>(L, pass);
+    m[1] = two_sweep_diameter<S>(L, pass, comp);
   } else if constexpr (PROBLEM == kMaze) {
     W r;
     int d = nearest<S>(L, channel_row<PROBLEM, W>(p, in, 2), channel_row<PROBLEM, W>(p, in, 3), pass, r);
@@ -1039,8 +1064,12 @@ __global__ __launch_bounds__(64) void init_kernel(KArgs a) {
   const W inside = inside_row<W>(L.y, h, w);
   if (a.flags & kInitMetrics) {
     int m[PR::M];
-    full_metrics<S, PROBLEM>(L, p, inside, wm.valid, m);
+    W comp;
+    full_metrics<S, PROBLEM>(L, p, inside, wm.valid, m, comp);
     if (wm.primary && L.y == 0) store_metrics<S, PROBLEM>(a.metrics + (size_t)wm.env * kMaxMetrics, m);
+    if constexpr (PROBLEM == kBinary) {  // (the plane after the tile planes)
+      if (wm.primary) planes[(size_t)PR::P * a.plane_stride + ridx] = comp;
+    }
   }
   if ((a.flags & kInitTargets) && wm.primary && L.y < PR::M) {
     uint32_t t = pack_range(a.target_lo[L.y], a.target_hi[L.y]);
@@ -1084,7 +1113,8 @@ __global__ __launch_bounds__(64) void exact_diameter_kernel(KArgs a, int32_t* ou
 // The observation wavefront of the split kernel: loads the level, applies the edit in registers
 // (it stores nothing but the observation), finds the agent's next cell and writes the window
 // around it.  It reads what the metrics wavefront of the same workgroup reads, and the workgroup
-// barrier keeps that wavefront from storing the new state before these loads were issued.
+// barrier, which this wavefront enters only when its loads have returned, keeps that wavefront
+// from storing the new state before.
 template <int S, int PROBLEM>
 __device__ __forceinline__ void obs_wave_step(const KArgs& a, const Lanes<S>& L, const WaveMap<S>& wm) {
   using W = typename RowWord<S>::T;
@@ -1103,16 +1133,20 @@ __device__ __forceinline__ void obs_wave_step(const KArgs& a, const Lanes<S>& L,
   const uint4* erp = reinterpret_cast<const uint4*>(a.env + wm.envl);
   const uint4 er0 = erp[0], er1 = erp[1];
   const int act = a.actions[wm.envl];
-  // the barrier as soon as the loads are issued (the metrics wavefront waits there for nothing
-  // else), fenced off so that no use of a loaded value, with its wait, moves in front of it
+  // where the observation goes is worked out, and its staging words are cleared, while the loads
+  // are in flight (fenced off so that no use of a loaded value, with its wait, moves in between)
   __builtin_amdgcn_sched_barrier(0);
-  __syncthreads();
-  __builtin_amdgcn_sched_barrier(0);
-  if (!(a.use_frozen & 2)) fz = 0;
   ObsPlan pl = obs_plan(a, L.lane, wm.sl, a.obs, wm.env0, wm.nvalid);
   obs_plan_pin(pl);
   obs_clear(wm.lds, L.lane, pl);
   __builtin_amdgcn_sched_barrier(0);
+  // The barrier only once every load of the old state has returned: the metrics wavefront stores
+  // the new state after it, and nothing else orders those stores behind these loads.  (That
+  // wavefront requested the same words at the same time, so it would be waiting for them anyway.)
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  __builtin_amdgcn_sched_barrier(0);
+  if (!(a.use_frozen & 2)) fz = 0;
 
   int h = (int)(er0.x & 0xffu), w = (int)((er0.x >> 8) & 0xffu);
   const int py = (int)((er0.x >> 16) & 0xffu), px = (int)(er0.x >> 24);
@@ -1189,7 +1223,10 @@ __device__ __forceinline__ void obs_wave_rollout(const KArgs& a, const Lanes<S>&
   const uint4 er0 = erp[0], er1 = erp[1];
   int act = a.actions[wm.envl];
   __builtin_amdgcn_sched_barrier(0);
-  __syncthreads();  // (the metrics wavefront stores the final state only after this)
+  // (the metrics wavefront stores the final state only after this barrier, and the barrier comes
+  // only after these loads have returned)
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
   __builtin_amdgcn_sched_barrier(0);
 
   int h = (int)(er0.x & 0xffu), w = (int)((er0.x >> 8) & 0xffu);
@@ -1312,6 +1349,11 @@ __global__ __launch_bounds__(MODE == kModeSplit || MODE == kModeRolloutSplit ? 3
   for (int i = 0; i < PR::P; ++i) p[i] = planes[(size_t)i * a.plane_stride + ridx];
   W fz = 0;  // pinpoint rows: resident only in a rollout; a single step keeps a flag with the cell
   if (ROLL || (a.use_frozen & 2)) fz = frozen[ridx];
+  // binary problem: the component of the first walkable cell, which is all that the diameter
+  // estimate depends on; an edit elsewhere needs no sweep (see diameter_untouched)
+  W comp = 0;
+  bool comp_dirty = false;
+  if constexpr (PROBLEM == kBinary) comp = planes[(size_t)PR::P * a.plane_stride + ridx];
   const uint4* erp = reinterpret_cast<const uint4*>(a.env + wm.envl);
   const uint4 er0 = erp[0], er1 = erp[1];  // unpacked below, after all loads are under way
   int act = a.actions[wm.envl];  // (lanes without a level of their own read a neighbour's and ignore it)
@@ -1328,8 +1370,8 @@ __global__ __launch_bounds__(MODE == kModeSplit || MODE == kModeRolloutSplit ? 3
   const float w_l = __uint_as_float((a.targets - kMaxMetrics)[yi]);  // (the row in front of the ranges)
   // every load above is issued before anything below waits for one of them
   __builtin_amdgcn_sched_barrier(0);
-  // the observation wavefront has issued its loads of the old state before this wavefront goes
-  // on to store the new one (the barrier is passed with the loads still in flight)
+  // the observation wavefront has received the old state before this wavefront goes on to store
+  // the new one (this wavefront passes the barrier with its own loads still in flight)
   if constexpr (SPLIT) {
     __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
@@ -1460,8 +1502,21 @@ __global__ __launch_bounds__(MODE == kModeSplit || MODE == kModeRolloutSplit ? 3
       if (yi == 0) mn_l = regions_new;
       // paths
       if constexpr (PROBLEM == kBinary) {
-        int dm = two_sweep_diameter<S>(L, pass);
-        if (changed && yi == 1) mn_l = dm;
+        // (every modifying edit of a binary level flips the walkability of its cell)
+        const W cell = (changed && at_row) ? (W)1 << px : (W)0;
+        const bool need = changed && !diameter_untouched<S>(L, comp, cell, L.dilate(cell), py, px, now_pass);
+        if (wave_any<S>(need)) {
+          W ncomp;
+          int dm = two_sweep_diameter<S>(L, need ? pass : (W)0, ncomp);
+          if (need) {
+            comp = ncomp;
+            comp_dirty = true;
+            if (yi == 1) mn_l = dm;
+            if constexpr (!ROLL) {
+              if (wm.primary) planes[(size_t)PR::P * a.plane_stride + ridx] = ncomp;
+            }
+          }
+        }
       } else if constexpr (PROBLEM == kMaze) {
         W r;
         int dd = nearest<S>(L, channel_row<PROBLEM, W>(p, in, 2), channel_row<PROBLEM, W>(p, in, 3), pass, r);
@@ -1506,13 +1561,21 @@ __global__ __launch_bounds__(MODE == kModeSplit || MODE == kModeRolloutSplit ? 3
       begin_episode<S, PROBLEM, true>(ra, L, nkey, np, nfz, nh, nw, npy, npx, restart, wm.envl);
       W ninside = inside_row<W>(L.y, nh, nw);
       int nm[PR::M];
-      full_metrics<S, PROBLEM>(L, np, ninside, restart, nm);
+      W ncomp;
+      full_metrics<S, PROBLEM>(L, np, ninside, restart, nm, ncomp);
       if (restart) {
 #pragma unroll
         for (int i = 0; i < PR::P; ++i) {
           p[i] = np[i];
           if constexpr (!ROLL) {
             if (wm.primary) planes[(size_t)i * a.plane_stride + ridx] = np[i];
+          }
+        }
+        if constexpr (PROBLEM == kBinary) {
+          comp = ncomp;
+          comp_dirty = true;
+          if constexpr (!ROLL) {
+            if (wm.primary) planes[(size_t)PR::P * a.plane_stride + ridx] = ncomp;
           }
         }
         fz = nfz;
@@ -1578,6 +1641,9 @@ __global__ __launch_bounds__(MODE == kModeSplit || MODE == kModeRolloutSplit ? 3
         for (int i = 0; i < PR::P; ++i) planes[(size_t)i * a.plane_stride + ridx] = p[i];
       }
       if (fz_dirty) frozen[ridx] = fz;
+      if constexpr (PROBLEM == kBinary) {
+        if (comp_dirty) planes[(size_t)PR::P * a.plane_stride + ridx] = comp;
+      }
     }
     next_fz_row = L.gread(fz, py);
   }

@@ -767,6 +767,51 @@ def test_largest_batch_spot_check():
     gpu.close()
 
 
+@pytest.mark.parametrize("pos_mode", [wl.POS_SCAN, wl.POS_RANDOM], ids=["scan", "random"])
+def test_split_step_at_full_batch_for_thousands_of_steps(pos_mode):
+    """The step split into a metrics wavefront and an observation wavefront per workgroup, at the
+    benchmark batch, for 2000 steps: the observation wavefront reads the level that the metrics
+    wavefront of the same step overwrites, so every observation has to show the state after
+    exactly the edits so far.  Rewards, done flags and metrics of every step (all levels),
+    observations and the whole state every 50th step; the oracle is sharded over host threads."""
+    from concurrent.futures import ThreadPoolExecutor
+    dev = torch.device("cuda", 0)
+    steps, B, chunk, shards = 2000, 4096, 50, 8
+    cfg = wl.workload("maze16", batch=B, max_steps=700, pos_mode=pos_mode, split_step=2)
+    print(f"[split long] pos_mode={pos_mode} batch={B} steps={steps}", flush=True)
+    gpu, cpu = binding.Pcgrl(cfg, 0), oracle.Oracle(cfg)
+    obs = gpu.new_obs()
+    gpu.pcgrl_reset(5, obs)
+    cpu.reset(5, want_obs=False)
+    acts_np = wl.random_actions(cfg, 6, steps)
+    acts = torch.from_numpy(acts_np).to(dev)
+    rew = torch.empty((chunk, B), dtype=torch.float32, device=dev)
+    done = torch.empty((chunk, B), dtype=torch.uint8, device=dev)
+    met = torch.empty((chunk, B, gpu.M), dtype=torch.int32, device=dev)
+    c_obs = cpu.new_obs()
+    c_rew = np.zeros((chunk, B), np.float32)
+    c_done = np.zeros((chunk, B), np.uint8)
+    c_met = np.zeros((chunk, B, gpu.M), np.int32)
+    bounds = [(i * B // shards, (i + 1) * B // shards) for i in range(shards)]
+    with ThreadPoolExecutor(shards) as pool:
+        for t0 in range(0, steps, chunk):
+            for k in range(chunk):
+                gpu.pcgrl_step(acts[t0 + k], obs, rew[k], done[k])
+                gpu.pcgrl_metrics(met[k])
+            for k in range(chunk):
+                o = c_obs if k == chunk - 1 else None      # the oracle writes the window only where it is compared
+                list(pool.map(lambda b: cpu.step_range(b[0], b[1], acts_np[t0 + k], o, c_rew[k], c_done[k]), bounds))
+                c_met[k] = cpu.metrics()
+            ctx = f"steps {t0}..{t0 + chunk - 1}"
+            assert np.array_equal(rew.cpu().numpy(), c_rew), "reward " + ctx
+            assert np.array_equal(done.cpu().numpy(), c_done), "done " + ctx
+            assert np.array_equal(met.cpu().numpy(), c_met), "metrics " + ctx
+            assert_same("obs", obs, c_obs, f"step {t0 + chunk - 1}")
+            compare_state(gpu, cpu, f"step {t0 + chunk - 1}")
+            print(f"[split long] {ctx} ok", flush=True)
+    gpu.close()
+
+
 LONG = [
     ("maze16", wl.workload("maze16", batch=96, max_steps=3000), 4000),
     ("binary16", wl.workload("binary16", batch=64, max_steps=1000), 2500),
