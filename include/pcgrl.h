@@ -199,9 +199,11 @@ int pcgrl_metrics(pcgrl_ctx* ctx, int32_t* out, void* stream);
 
 /* Exact diameter of every level: the largest shortest-path distance between any two connected
  * walkable cells (the graph diameter that the two-sweep estimate of Task / Binary domain stands
- * for), by a breadth-first sweep from every walkable cell.  A diagnostic for the error of the two-sweep
- * estimate, not part of a step: the cost grows with (walkable cells) x (eccentricity), about a
- * million vector instructions for one open 64x64 level.  out: device, int32 [batch]. */
+ * for), by a breadth-first sweep from every walkable cell.  A diagnostic for the error of the
+ * two-sweep estimate, not part of a step: the cost grows with (walkable cells) x (eccentricity),
+ * about a million vector instructions for one open 64x64 level.  For small batches the sources of
+ * a level are shared out over several workgroups, whose partial results go through a buffer that
+ * the context owns.  out: device, int32 [batch]. */
 int pcgrl_exact_diameter(pcgrl_ctx* ctx, int32_t* out, void* stream);
 
 /* Writes the current observation of every environment without stepping.  obs: device. */

@@ -37,6 +37,8 @@ struct pcgrl_ctx {
   void* d_metrics;
   void* d_targets;
   void* d_bad;
+  void* d_exact;         // partial results of pcgrl_exact_diameter, [1 << exact_parts_log2][batch] ints (NULL for one part)
+  int exact_parts_log2;  // a level's sources are shared out over this many workgroups there
 };
 
 namespace {
@@ -131,11 +133,31 @@ template <int S, int PROBLEM> struct LaunchInit {
 };
 
 template <int S, int PROBLEM> struct LaunchExact {
-  static int run(const pcgrl_ctx* ctx, const KArgs& a, int32_t* out, hipStream_t st) {
-    hipLaunchKernelGGL((exact_diameter_kernel<S, PROBLEM>), dim3(ctx->nwaves), dim3(64), ctx->lds_bytes, st, a, out);
+  static int run(const pcgrl_ctx* ctx, const KArgs& a, int32_t* out, int parts_log2, hipStream_t st) {
+    hipLaunchKernelGGL((exact_diameter_kernel<S, PROBLEM>), dim3((unsigned)ctx->nwaves << parts_log2), dim3(64),
+                       ctx->lds_bytes, st, a, out, parts_log2);
     return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
   }
 };
+
+// Exact diameters into `out`, the sources of every level shared out over 1 << parts_log2
+// workgroups whose partial results go through `partial` ([parts][batch] ints, unused for one part).
+int exact_diameter_with(pcgrl_ctx* ctx, int32_t* out, int32_t* partial, int parts_log2, hipStream_t st) {
+  if (parts_log2 == 0) return dispatch<LaunchExact>(ctx->S, ctx->cfg.problem, ctx, ctx->base, out, 0, st);
+  int rc = dispatch<LaunchExact>(ctx->S, ctx->cfg.problem, ctx, ctx->base, partial, parts_log2, st);
+  if (rc != PCGRL_OK) return rc;
+  const int B = ctx->cfg.batch;
+  hipLaunchKernelGGL(max_over_parts_kernel, dim3((B + 255) / 256), dim3(256), 0, st, partial, out, B, 1 << parts_log2);
+  return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
+}
+
+// Into how many parts (a power of two, at most one per row) pcgrl_exact_diameter splits the
+// sources of a level: enough for about four thousand wavefronts.
+int exact_parts_for(int nwaves, int S) {
+  int lg = 0;
+  while ((1 << (lg + 1)) <= S && ((long long)nwaves << (lg + 1)) <= 4096) ++lg;
+  return lg;
+}
 
 int launch_init(pcgrl_ctx* ctx, int flags, uint64_t seed, uint8_t* obs, hipStream_t st) {
   KArgs a = ctx->base;
@@ -357,6 +379,7 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   ctx->roll_lds_wave = lds_for(ctx->roll_o);
   if (ctx->roll_lds_wave * (ctx->roll_m / ctx->roll_o) > 64 * 1024) ctx->split_roll = 0;
 
+  ctx->exact_parts_log2 = exact_parts_for(ctx->nwaves, ctx->S);
   const size_t rows = (size_t)ctx->B_pad * ctx->S;
   struct { void** p; size_t n; } allocs[] = {
       // (the binary problem keeps one more plane: the component of the first walkable cell)
@@ -368,9 +391,11 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
       // through the one pointer it has at hand when it issues its loads)
       {&ctx->d_targets, ((size_t)ctx->B_pad + 1) * kMaxMetrics * sizeof(uint32_t)},
       {&ctx->d_bad, sizeof(unsigned long long)},
+      {&ctx->d_exact, ctx->exact_parts_log2 ? ((size_t)cfg->batch << ctx->exact_parts_log2) * sizeof(int32_t) : 0},
   };
   for (auto& al : allocs) *al.p = nullptr;
   for (auto& al : allocs) {
+    if (al.n == 0) continue;
     if (hipMalloc(al.p, al.n) != hipSuccess || hipMemset(*al.p, 0, al.n) != hipSuccess) {
       for (auto& f : allocs)
         if (*f.p) (void)hipFree(*f.p);
@@ -388,7 +413,8 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   a.targets = static_cast<uint32_t*>(ctx->d_targets) + kMaxMetrics;
   a.bad_actions = static_cast<unsigned long long*>(ctx->d_bad);
   if (hipMemcpy(ctx->d_targets, cfg->weights, kMaxMetrics * sizeof(float), hipMemcpyHostToDevice) != hipSuccess) {
-    for (auto& f : allocs) (void)hipFree(*f.p);
+    for (auto& f : allocs)
+      if (*f.p) (void)hipFree(*f.p);
     delete ctx;
     return PCGRL_E_HIP;
   }
@@ -463,7 +489,7 @@ int pcgrl_destroy(pcgrl_ctx* ctx) {
   if (!ctx) return PCGRL_OK;
   DeviceGuard guard(ctx->device);  // (freed in any case)
   int rc = guard.ok && hipDeviceSynchronize() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
-  void* bufs[] = {ctx->d_planes, ctx->d_frozen, ctx->d_env, ctx->d_metrics, ctx->d_targets, ctx->d_bad};
+  void* bufs[] = {ctx->d_planes, ctx->d_frozen, ctx->d_env, ctx->d_metrics, ctx->d_targets, ctx->d_bad, ctx->d_exact};
   for (void* b : bufs)
     if (b && hipFree(b) != hipSuccess) rc = PCGRL_E_HIP;
   delete ctx;
@@ -552,7 +578,8 @@ int pcgrl_exact_diameter(pcgrl_ctx* ctx, int32_t* out, void* stream) {
   if (!ctx || !out) return PCGRL_E_NULL;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return PCGRL_E_DEVICE;
-  return dispatch<LaunchExact>(ctx->S, ctx->cfg.problem, ctx, ctx->base, out, static_cast<hipStream_t>(stream));
+  return exact_diameter_with(ctx, out, static_cast<int32_t*>(ctx->d_exact), ctx->exact_parts_log2,
+                             static_cast<hipStream_t>(stream));
 }
 
 int pcgrl_observe(pcgrl_ctx* ctx, uint8_t* obs, void* stream) {

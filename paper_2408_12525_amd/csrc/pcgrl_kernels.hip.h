@@ -1080,17 +1080,21 @@ __global__ __launch_bounds__(64) void init_kernel(KArgs a) {
     observe<S, PROBLEM>(a, L, wm, obs_plan(a, L.lane, wm.sl, a.obs, wm.env0, wm.nvalid), p, fz, inside, py, px);
 }
 
-// Exact diameter: a sweep from every walkable cell, the largest eccentricity found.  Cells are
+// Exact diameter: a sweep from every walkable cell, the largest eccentricity found.  The sources
+// of a level are shared out over 1 << parts_log2 workgroups by their row (row y goes to part
+// y mod parts); each writes the largest eccentricity among its sources to out[part][env], and
+// max_over_parts_kernel folds the parts (with one part, out is the result itself).  Cells are
 // taken in row-major order, each group at its own pace; the loop ends when no group has a cell
 // left (every sweep ends because its visited set can only grow).
 template <int S, int PROBLEM>
-__global__ __launch_bounds__(64) void exact_diameter_kernel(KArgs a, int32_t* out) {
+__global__ __launch_bounds__(64) void exact_diameter_kernel(KArgs a, int32_t* out, int parts_log2) {
   using W = typename RowWord<S>::T;
   using PR = Prob<PROBLEM>;
   extern __shared__ uint32_t lds_all[];
   Lanes<S> L;
   WaveMap<S> wm;
-  wm.init(a, L, lds_all, level_group_of_block<false>(0), a.envs_per_wave_log2 & 0xff);
+  const int part = (int)blockIdx.x & ((1 << parts_log2) - 1);
+  wm.init(a, L, lds_all, (int)blockIdx.x >> parts_log2, a.envs_per_wave_log2 & 0xff);
   const W* planes = reinterpret_cast<const W*>(a.planes);
   const size_t ridx = (size_t)wm.envl * S + L.y;
   W p[PR::P];
@@ -1099,7 +1103,7 @@ __global__ __launch_bounds__(64) void exact_diameter_kernel(KArgs a, int32_t* ou
   const EnvRec er = a.env[wm.envl];
   const W inside = wm.valid ? inside_row<W>(L.y, er.h, er.w) : (W)0;
   const W pass = inside & ~channel_row<PROBLEM, W>(p, inside, 1);
-  W todo = pass;
+  W todo = (L.y & ((1 << parts_log2) - 1)) == part ? pass : (W)0;
   int best = 0;
   for (;;) {
     const W src = first_cell<S>(L, todo);
@@ -1107,7 +1111,16 @@ __global__ __launch_bounds__(64) void exact_diameter_kernel(KArgs a, int32_t* ou
     todo &= ~src;
     best = max(best, eccentricity<S>(L, src, pass));
   }
-  if (wm.primary && L.y == 0) out[wm.env] = best;
+  if (wm.primary && L.y == 0) out[(size_t)part * (size_t)a.B + wm.env] = best;
+}
+
+// out[env] = max over parts of partial[part][env]
+__global__ void max_over_parts_kernel(const int32_t* partial, int32_t* out, int B, int parts) {
+  const int env = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+  if (env >= B) return;
+  int best = 0;
+  for (int q = 0; q < parts; ++q) best = max(best, partial[(size_t)q * B + env]);
+  out[env] = best;
 }
 
 // The observation wavefront of the split kernel: loads the level, applies the edit in registers
