@@ -48,6 +48,7 @@ extern "C" {
 #define PCGRL_E_HIP (-3)      /* a HIP runtime call failed */
 #define PCGRL_E_NOMEM (-4)    /* device allocation failed */
 #define PCGRL_E_DEVICE (-5)   /* the device is not a gfx950 part, does not exist or cannot be made current */
+#define PCGRL_E_SCRATCH (-6)  /* pcgrl_exact_diameter_static: more partial results than its static array holds */
 
 #define PCGRL_BINARY 0
 #define PCGRL_MAZE 1
@@ -205,6 +206,20 @@ int pcgrl_metrics(pcgrl_ctx* ctx, int32_t* out, void* stream);
  * a level are shared out over several workgroups, whose partial results go through a buffer that
  * the context owns.  out: device, int32 [batch]. */
 int pcgrl_exact_diameter(pcgrl_ctx* ctx, int32_t* out, void* stream);
+
+/* pcgrl_exact_diameter for callers that cannot allocate device memory and want nothing allocated
+ * on their behalf (code under HIP graph capture, tight serving loops, harnesses that forbid it):
+ * the same kernels and the same results, with the partial results (one int per level and part) in
+ * a static device array of the library, 1 MiB = 262 144 ints per GPU, held until the process ends,
+ * instead of the context's own buffer.  Calls no allocating routine.
+ *   parts_log2: a level's sources are shared out over 1 << parts_log2 workgroups (at most one per
+ *               row of the 16 / 32 / 64-row buffer); -1 = what pcgrl_exact_diameter uses.
+ * Errors: E_NULL; E_CONFIG if parts_log2 is out of range; E_SCRATCH if batch << parts_log2 exceeds
+ * 262 144 (with one part the array is not used and any batch is accepted).
+ * Every call on a GPU shares that GPU's array: calls that overlap on one GPU (different streams or
+ * contexts) race; calls ordered on one stream do not.  Nothing in the array has to start at zero
+ * (every word that is read was written by the same call). */
+int pcgrl_exact_diameter_static(pcgrl_ctx* ctx, int32_t* out, int32_t parts_log2, void* stream);
 
 /* Writes the current observation of every environment without stepping.  obs: device. */
 int pcgrl_observe(pcgrl_ctx* ctx, uint8_t* obs, void* stream);

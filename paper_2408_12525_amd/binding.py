@@ -43,7 +43,7 @@ class PcgrlConfig(C.Structure):
 
 EXPORTS = [
     "pcgrl_config_default", "pcgrl_create", "pcgrl_destroy", "pcgrl_reset", "pcgrl_step", "pcgrl_rollout",
-    "pcgrl_metrics", "pcgrl_exact_diameter", "pcgrl_observe", "pcgrl_get_state", "pcgrl_set_state", "pcgrl_set_targets",
+    "pcgrl_metrics", "pcgrl_exact_diameter", "pcgrl_exact_diameter_static", "pcgrl_observe", "pcgrl_get_state", "pcgrl_set_state", "pcgrl_set_targets",
     "pcgrl_get_targets",
     "pcgrl_obs_shape", "pcgrl_obs_bytes", "pcgrl_obs_stride", "pcgrl_num_metrics", "pcgrl_num_tiles", "pcgrl_bad_action_count",
     "pcgrl_selftest", "pcgrl_store_rate", "pcgrl_strerror",
@@ -84,6 +84,7 @@ def load():
     L.pcgrl_metrics.argtypes = [p, p, p]
     L.pcgrl_observe.argtypes = [p, p, p]
     L.pcgrl_exact_diameter.argtypes = [p, p, p]
+    L.pcgrl_exact_diameter_static.argtypes = [p, p, i32, p]
     L.pcgrl_get_state.argtypes = [p, p, p, p, p, p, p]
     L.pcgrl_set_state.argtypes = [p, p, p, p, p, p]
     L.pcgrl_set_targets.argtypes = [p, p, p]
@@ -254,6 +255,11 @@ class Pcgrl:
             out = torch.empty((self.B,), dtype=torch.int32, device=self.device)
         o = self._dev(out, torch.int32, (self.B,), "out")
         _check(self.L.pcgrl_exact_diameter(self.h, o, self._st()), "pcgrl_exact_diameter")
+        return out
+
+    def pcgrl_exact_diameter_static(self, out, parts_log2: int = -1):
+        o = self._dev(out, torch.int32, (self.B,), "out")
+        _check(self.L.pcgrl_exact_diameter_static(self.h, o, parts_log2, self._st()), "pcgrl_exact_diameter_static")
         return out
 
     def pcgrl_observe(self, obs=None):

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "pcgrl_kernels.hip.h"
@@ -151,6 +152,28 @@ int exact_diameter_with(pcgrl_ctx* ctx, int32_t* out, int32_t* partial, int part
   return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
 }
 
+// Partial results of pcgrl_exact_diameter_static, for callers that must not allocate: one array per
+// GPU the library runs on, held until the process ends.  The name is a host-side stand-in, not a
+// device address; host code uses only the address hipGetSymbolAddress gives for the current device.
+constexpr size_t kStaticScratchInts = (size_t)1 << 18;  // 1 MiB
+__device__ __align__(256) int32_t scratch[kStaticScratchInts];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+int32_t* g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each GPU, once asked for
+
+// The device address of `scratch` on `device`, which must be the current device.
+int static_scratch(int device, int32_t** out) {
+  if (device < 0 || device >= kMaxDevices) return PCGRL_E_DEVICE;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return PCGRL_E_HIP;
+    g_scratch_ptr[device] = static_cast<int32_t*>(ptr);
+  }
+  *out = g_scratch_ptr[device];
+  return PCGRL_OK;
+}
+
 // Into how many parts (a power of two, at most one per row) pcgrl_exact_diameter splits the
 // sources of a level: enough for about four thousand wavefronts.
 int exact_parts_for(int nwaves, int S) {
@@ -205,6 +228,7 @@ const char* pcgrl_strerror(int code) {
     case PCGRL_E_HIP: return "HIP runtime call failed";
     case PCGRL_E_NOMEM: return "device allocation failed";
     case PCGRL_E_DEVICE: return "no such device, or not a gfx950 device";
+    case PCGRL_E_SCRATCH: return "the call needs more partial results than the library's static scratch array holds";
     default: return "unknown error code";
   }
 }
@@ -580,6 +604,22 @@ int pcgrl_exact_diameter(pcgrl_ctx* ctx, int32_t* out, void* stream) {
   if (!guard.ok) return PCGRL_E_DEVICE;
   return exact_diameter_with(ctx, out, static_cast<int32_t*>(ctx->d_exact), ctx->exact_parts_log2,
                              static_cast<hipStream_t>(stream));
+}
+
+int pcgrl_exact_diameter_static(pcgrl_ctx* ctx, int32_t* out, int32_t parts_log2, void* stream) {
+  if (!ctx || !out) return PCGRL_E_NULL;
+  if (parts_log2 < -1 || (parts_log2 >= 0 && (1 << parts_log2) > ctx->S)) return PCGRL_E_CONFIG;
+  const int lg = parts_log2 < 0 ? ctx->exact_parts_log2 : parts_log2;
+  const size_t need = lg ? ((size_t)ctx->cfg.batch << lg) : 0;  // ints of partial results
+  if (need > kStaticScratchInts) return PCGRL_E_SCRATCH;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return PCGRL_E_DEVICE;
+  int32_t* partial = nullptr;
+  if (lg) {
+    const int rc = static_scratch(ctx->device, &partial);
+    if (rc != PCGRL_OK) return rc;
+  }
+  return exact_diameter_with(ctx, out, partial, lg, static_cast<hipStream_t>(stream));
 }
 
 int pcgrl_observe(pcgrl_ctx* ctx, uint8_t* obs, void* stream) {
