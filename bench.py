@@ -29,6 +29,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 VALU_PEAK_GINST = 256 * 4 * 2.4 / 4.0
 MIN_REP_MS = 5.0       # a timed repetition lasts at least this long (the graph is replayed)
 MALL_BYTES = 256 << 20  # memory-side cache: an observation ring has to be well beyond it
+ACTION_STREAM_BYTES = 32 << 20  # the pre-generated actions of a run stay below this
 
 
 def state_bytes_per_env(cfg) -> int:
@@ -144,6 +145,8 @@ class GpuRun:
         if args.max_changes is not None:
             cfg["max_changes"] = args.max_changes
         cfg["obs_pitch"] = -1 if args.obs_pitch == "lines" else 0
+        cfg["split_step"] = ["auto", "off", "on"].index(args.split)
+        cfg["levels_per_wave"] = args.levels_per_wave
         self.cfg, self.name, self.args = cfg, name, args
         self.B = cfg["batch"]
         self.tag = f"{name}_B{self.B}"
@@ -170,10 +173,15 @@ class GpuRun:
         slice of the action stream and its own observation slot); a repetition replays the graph
         until it has lasted MIN_REP_MS.  Returns wall and HIP-event time per step."""
         torch, wl, env, args = self.torch, self.wl, self.env, self.args
-        n_act = min(K, 1000)   # the action stream repeats after 1000 steps (keeps it small in HBM)
+        # The pre-generated action stream repeats after 1000 steps, or sooner where 1000 steps of it
+        # would not stay in the memory-side cache: a policy in the loop hands over actions that a
+        # kernel has just written, not ones that have to come from HBM behind the step's own writes
+        # (measured on the 16x16 binary problem at a batch of 262 144: 92 against 109 us per step).
+        n_act = max(1, min(K, 1000, max(16, ACTION_STREAM_BYTES // (4 * self.B))))
+        n_warm = max(1, min(W, n_act))
         acts = torch.from_numpy(wl.random_actions(self.cfg, aseed, n_act)).to(self.dev)
-        warm = torch.from_numpy(wl.random_actions(self.cfg, aseed + 1, max(W, 1))).to(self.dev)
-        chunk = min(n_act, K)
+        warm = torch.from_numpy(wl.random_actions(self.cfg, aseed + 1, n_warm)).to(self.dev)
+        chunk = min(1000, K)   # kernel nodes of one graph
         while K % chunk:
             chunk -= 1
         one = self.B * self.obs_stride
@@ -189,7 +197,7 @@ class GpuRun:
                 env.pcgrl_reset(seed, ring[0])
                 with torch.cuda.graph(graph, stream=side):
                     for t in range(chunk):
-                        env.pcgrl_step(acts[t], ring[t % slots], self.rew, self.done)
+                        env.pcgrl_step(acts[t % n_act], ring[t % slots], self.rew, self.done)
             torch.cuda.current_stream().wait_stream(side)
             torch.cuda.synchronize()
 
@@ -205,7 +213,7 @@ class GpuRun:
         for rep in range(reps):
             env.pcgrl_reset(seed, ring[0])
             for t in range(W):
-                env.pcgrl_step(warm[t], ring[t % slots], self.rew, self.done)
+                env.pcgrl_step(warm[t % n_warm], ring[t % slots], self.rew, self.done)
             if rep == 0:               # how many rounds of K steps make a repetition long enough
                 torch.cuda.synchronize()
                 t0 = time.perf_counter()
@@ -224,6 +232,9 @@ class GpuRun:
             torch.cuda.synchronize()
             times_ms.append((time.perf_counter() - t0) * 1e3)
             ev_ms.append(e0.elapsed_time(e1))
+        if os.environ.get("PCGRL_BENCH_VERBOSE"):
+            print(f"[bench] {self.tag}: us/step per repetition {[round(t * 1e3 / (K * rounds), 2) for t in ev_ms]}, "
+                  f"rounds {rounds}, slots {slots}", file=sys.stderr)
         order = sorted(range(reps), key=lambda i: times_ms[i])
         mid = order[len(order) // 2]
         n = K * rounds
@@ -307,7 +318,7 @@ def summarise(run: GpuRun, step, roll):
     valu_frac = valu / launch_s / 1e9 / VALU_PEAK_GINST if valu else None
     hbm_frac = achieved / HBM_PEAK_GBS
     # which ceiling is nearer: the launch itself (an empty launch is 1.5 us), the vector ALUs, or HBM
-    if launch_s < 3.0e-6 and hbm_frac < 0.1:
+    if launch_s < 6.0e-6 and hbm_frac < 0.05:
         bound = "launch"
     elif valu_frac is not None and valu_frac > hbm_frac:
         bound = "alu"
@@ -357,6 +368,10 @@ def main():
     ap.add_argument("--obs-pitch", choices=["dense", "lines"], default="lines",
                     help="observation layout: one level's observation directly after the other, or "
                          "every level's observation padded to whole 128-byte lines (obs_pitch; default)")
+    ap.add_argument("--split", choices=["auto", "off", "on"], default="auto",
+                    help="tuning: one wavefront per level group, or a metrics and an observation wavefront")
+    ap.add_argument("--levels-per-wave", type=int, default=0, choices=[0, 1, 2, 4],
+                    help="tuning: levels packed into one wavefront (0 = the library's rule)")
     ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
                     help="replay a HIP graph of pcgrl_step launches (default) or call it from Python")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")

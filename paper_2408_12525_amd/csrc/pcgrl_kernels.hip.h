@@ -1248,6 +1248,7 @@ __device__ __forceinline__ void obs_wave_rollout(const KArgs& a, const Lanes<S>&
   uint64_t key = (uint64_t)er1.x | ((uint64_t)er1.y << 32);
   W inside = inside_row<W>(L.y, h, w);
   const int nsteps = a.rollout_steps;
+  int slot = 0;
   for (int step = 0; step < nsteps; ++step) {
     int act_next = -1;
     if (step + 1 < nsteps) act_next = a.actions[(size_t)(step + 1) * a.B + wm.envl];
@@ -1303,7 +1304,8 @@ __device__ __forceinline__ void obs_wave_rollout(const KArgs& a, const Lanes<S>&
         n_changes = 0;
       }
     }
-    uint8_t* obs = a.obs + (size_t)(step % a.obs_slots) * (size_t)a.B * (size_t)a.env_obs_bytes;
+    uint8_t* obs = a.obs + (size_t)slot * (size_t)a.B * (size_t)a.env_obs_bytes;
+    slot = slot + 1 == a.obs_slots ? 0 : slot + 1;  // (step t writes slot t mod obs_slots)
     observe<S, PROBLEM, false, true>(a, L, wm, obs_plan(a, L.lane, wm.sl, obs, wm.env0, wm.nvalid), p, fz, inside, qy,
                                      qx);
     py = qy;
@@ -1413,6 +1415,7 @@ __global__ __launch_bounds__(MODE == kModeSplit || MODE == kModeRolloutSplit ? 3
   uint32_t next_cell_frozen = 0;
 
   const int nsteps = ROLL ? a.rollout_steps : 1;
+  [[maybe_unused]] int slot = 0;
   for (int step = 0; step < nsteps; ++step) {
     // the next step's action is requested now and used one iteration later
     int act_next = -1;
@@ -1422,7 +1425,8 @@ __global__ __launch_bounds__(MODE == kModeSplit || MODE == kModeRolloutSplit ? 3
     uint8_t* obs = a.obs;
     if constexpr (ROLL && !SPLIT) {
       if (obs != nullptr) {
-        obs += (size_t)(step % a.obs_slots) * (size_t)a.B * (size_t)a.env_obs_bytes;
+        obs += (size_t)slot * (size_t)a.B * (size_t)a.env_obs_bytes;
+        slot = slot + 1 == a.obs_slots ? 0 : slot + 1;  // (step t writes slot t mod obs_slots)
         pl = obs_plan(a, L.lane, wm.sl, obs, wm.env0, wm.nvalid);
       }
     }
