@@ -151,17 +151,22 @@ typedef struct {
 int pcgrl_config_default(int32_t problem, pcgrl_config* cfg);
 
 /* Creates a context on GPU `device` and allocates all device state (about
- * 3*S*8 + 170 bytes per environment, S = 16, 32 or 64 covering max_h and max_w).  The
- * environments start as if pcgrl_reset(seed = 0) had been called.  Synchronises.
+ * 3*S*8 + 170 bytes per environment, S = 16, 32 or 64 covering max_h and max_w): the many
+ * environments that are stepped in lockstep on one GPU (Methods / Jax implementation; no passage
+ * defines the call itself).  The environments start as if pcgrl_reset(seed = 0) had been called.
+ * Synchronises.
  * cfg, out: host pointers.  Errors: E_NULL, E_CONFIG, E_DEVICE, E_NOMEM, E_HIP. */
 int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device);
 
-/* Frees the context and its device memory.  Synchronises the device first.  NULL is accepted. */
+/* Frees the context and its device memory (no passage of the paper: resource management).
+ * Synchronises the device first.  NULL is accepted. */
 int pcgrl_destroy(pcgrl_ctx* ctx);
 
-/* Starts episode 0 of every environment from `seed`: shape, tiles, pinpoints, first position
- * (all from a counter-based generator keyed by seed, global environment index and episode, so
- * results do not depend on batch size), default target ranges, full metrics.
+/* Starts episode 0 of every environment from `seed` (Methods / Task: the initial map is drawn
+ * tile by tile from a weighted distribution, or left empty; Task / Randomized map shapes; Task /
+ * Pinpoint tiles): shape, tiles, pinpoints, first position (all from a counter-based generator
+ * keyed by seed, global environment index and episode, so results do not depend on batch size),
+ * default target ranges, full metrics.
  * obs: device pointer, uint8 [batch][C][obs_w][obs_w], or NULL to skip the observation. */
 int pcgrl_reset(pcgrl_ctx* ctx, uint64_t seed, uint8_t* obs, void* stream);
 
@@ -178,7 +183,10 @@ int pcgrl_reset(pcgrl_ctx* ctx, uint64_t seed, uint8_t* obs, void* stream);
  *   done   : device, uint8 [batch].
  * reward and done may be NULL.
  * The call only enqueues one kernel launch, so it may be captured into a HIP graph; a captured
- * launch keeps the arguments and the reset seed that were current when it was captured. */
+ * launch keeps the arguments, the reset seed and the context's host-side settings that were
+ * current when it was captured: capture again after pcgrl_reset with another seed and after a
+ * pcgrl_set_state that passes a frozen mask to a context configured without pinpoints (from then
+ * on steps look pinpoints up, which launches captured before do not). */
 int pcgrl_step(pcgrl_ctx* ctx, const int32_t* actions, uint8_t* obs, float* reward, uint8_t* done,
                void* stream);
 
@@ -191,11 +199,13 @@ int pcgrl_step(pcgrl_ctx* ctx, const int32_t* actions, uint8_t* obs, float* rewa
  *            (obs_slots = n_steps keeps every observation, 1 keeps only the last).  May be NULL.
  *   reward : device, float32 [n_steps][batch], may be NULL
  *   done   : device, uint8 [n_steps][batch], may be NULL
- * Errors: E_NULL; E_CONFIG if n_steps < 1 or obs_slots is not in 1..n_steps. */
+ * Errors: E_NULL; E_CONFIG if n_steps is not in 1..2^20 or obs_slots is not in 1..n_steps. */
 int pcgrl_rollout(pcgrl_ctx* ctx, const int32_t* actions, int32_t n_steps, uint8_t* obs,
                   int32_t obs_slots, float* reward, uint8_t* done, void* stream);
 
-/* Copies the cached metric vectors.  out: device, int32 [batch][M]. */
+/* Copies the cached metric vectors: the region / path / tile-count measures of Methods / Task
+ * (Binary, Maze and Dungeon domains) that the reward is computed from, as listed at the top of
+ * this file.  out: device, int32 [batch][M]. */
 int pcgrl_metrics(pcgrl_ctx* ctx, int32_t* out, void* stream);
 
 /* Exact diameter of every level: the largest shortest-path distance between any two connected
@@ -221,10 +231,14 @@ int pcgrl_exact_diameter(pcgrl_ctx* ctx, int32_t* out, void* stream);
  * (every word that is read was written by the same call). */
 int pcgrl_exact_diameter_static(pcgrl_ctx* ctx, int32_t* out, int32_t parts_log2, void* stream);
 
-/* Writes the current observation of every environment without stepping.  obs: device. */
+/* Writes the current observation of every environment without stepping: the egocentric window of
+ * Methods / Training around the agent's cell, padded as Discussion (border tiles) describes, in
+ * the layout of pcgrl_step's `obs`.  obs: device. */
 int pcgrl_observe(pcgrl_ctx* ctx, uint8_t* obs, void* stream);
 
-/* Reads the environments back in a plain layout (all device pointers, any may be NULL):
+/* Reads the environments back in a plain layout -- the map of tiles an agent edits (Methods /
+ * Training), its frozen cells (Task / Pinpoint tiles) and its shape (Task / Randomized map shapes)
+ * (all device pointers, any may be NULL):
  *   tiles int8 [batch][max_h][max_w] (-1 outside the active map), frozen uint8 same shape,
  *   hw int16 [batch][2], pos int16 [batch][2], counters int32 [batch][3] = step count,
  *   modifying edits, episode number. */
@@ -246,11 +260,14 @@ int pcgrl_set_state(pcgrl_ctx* ctx, const int8_t* tiles, const uint8_t* frozen, 
  * episode starts. */
 int pcgrl_set_targets(pcgrl_ctx* ctx, const int32_t* targets, void* stream);
 
-/* Copies the target ranges now in force (a policy conditioned on control targets reads them
- * here).  out: device, int32 [batch][M][2]. */
+/* Copies the target ranges now in force (Methods / Training: a controllable generator observes
+ * the targets it is rewarded for approaching; a policy conditioned on them reads them here).
+ * out: device, int32 [batch][M][2]. */
 int pcgrl_get_targets(pcgrl_ctx* ctx, int32_t* out, void* stream);
 
-/* Shape queries (host side, no GPU work).  out: host pointer to 4 ints = batch, C, obs_w, obs_w. */
+/* Shape queries (host side, no GPU work).  The observation is one channel per tile type over the
+ * window of Methods / Training (plus the border channel of Discussion, plus the pinpoint channel
+ * if configured).  out: host pointer to 4 ints = batch, C, obs_w, obs_w. */
 int pcgrl_obs_shape(const pcgrl_ctx* ctx, int32_t out[4]);
 int64_t pcgrl_obs_bytes(const pcgrl_ctx* ctx); /* bytes of one level's observation in obs_format */
 int64_t pcgrl_obs_stride(const pcgrl_ctx* ctx); /* bytes from one level's observation to the next

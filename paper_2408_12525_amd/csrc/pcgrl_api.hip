@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cstdint>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -174,6 +175,58 @@ int static_scratch(int device, int32_t** out) {
   return PCGRL_OK;
 }
 
+// ---- launch shapes.  Results never depend on them; every row below is a measurement on MI355X
+// (per-step launches replayed from a HIP graph, rollouts of 100 steps; the figures are in the
+// design notes).  A rule table is read top down and the first row whose conditions all hold
+// decides; ranges are inclusive.
+constexpr int64_t kMax = INT64_MAX;
+constexpr int64_t kMB = (int64_t)1 << 20;
+struct SplitRule {
+  int S;                            // size class (16 / 32 / 64 rows), 0 = any
+  int64_t batch_lo, batch_hi;       // environments
+  int64_t obs_lo, obs_hi;           // bytes of one level's observation
+  int64_t step_lo, step_hi;         // bytes of one step's observations, whole batch
+  int problem;                      // -1 = any
+  int split;                        // 1: a metrics wavefront and observation wavefronts per workgroup
+};
+// pcgrl_step.  Two wavefronts per level group shorten the dependent chain of a launch at the price
+// of loading the level twice.
+const SplitRule kStepSplit[] = {
+    {16, 1, 8192, 0, kMax, 0, kMax, -1, 1},           // -10...-25 % per step at batches of 512...8192
+    {16, 8193, kMax, 3072, kMax, 256 * kMB + 1, 448 * kMB, -1, 0},  // stored through the cache: +17 %
+    {16, 8193, kMax, 1536, kMax, 0, kMax, -1, 1},     // maze16 -13 % at 12 288, -2...-4 % from 32 768; binary16 -3 % at 262 144
+    {32, 1, 4096, 0, kMax, 0, kMax, -1, 1},           // dungeon32 -16 % at 256, -7 % at 4096
+    {32, 4097, 16384, 8192, kMax, 0, kMax, -1, 1},    // 63-cell window (12 KB a level): -7 % at 16 384
+    {64, 1, 4096, 0, kMax, 0, kMax, -1, 1},           // maze64 -12 % at 256, -4 % at 4096; none from 8192 on
+    {0, 1, kMax, 0, kMax, 0, kMax, -1, 0},
+};
+// pcgrl_rollout (each wavefront keeps its own copy of the level for all the steps).
+const SplitRule kRolloutSplit[] = {
+    {16, 1, 2048, 0, kMax, 0, kMax, -1, 1},           // -35 % per step at 64 and 1024
+    {16, 2049, 12288, 0, 4095, 0, kMax, -1, 1},       // binary16 +39 % steps/s at 4096, +22 % at 8192
+    {16, 12289, kMax, 1536, 4095, 0, kMax, -1, 1},    // binary16 -5...-9 % per step from 16 384 to 131 072
+    {16, 2049, 4096, 4096, kMax, 0, kMax, -1, 1},     // maze16 -20 % at 4096
+    {16, 16384, kMax, 4096, kMax, 0, kMax, -1, 1},    // maze16 -2...-3 % (at 8192: +6 %, hence the gap)
+    {32, 1, 4096, 0, kMax, 0, kMax, -1, 1},           // -43 % at 256, -24 % at 4096
+    {32, 4097, kMax, 0, kMax, 0, kMax, PCGRL_BINARY, 1},  // +10 % steps/s at 16 384 (dungeon: +-2 %)
+    {64, 1, 8192, 0, kMax, 0, kMax, -1, 1},           // -6 %
+    {0, 1, kMax, 0, kMax, 0, kMax, -1, 0},
+};
+template <size_t N>
+int first_match(const SplitRule (&table)[N], int S, int64_t batch, int64_t obs, int64_t step_bytes, int problem) {
+  for (const SplitRule& r : table)
+    if ((r.S == 0 || r.S == S) && batch >= r.batch_lo && batch <= r.batch_hi && obs >= r.obs_lo && obs <= r.obs_hi &&
+        step_bytes >= r.step_lo && step_bytes <= r.step_hi && (r.problem < 0 || r.problem == problem))
+      return r.split;
+  return 0;
+}
+// As many levels per wavefront (a power of two up to G) as still leave `min_groups` wavefronts.
+int levels_per_wave_for(int G, int batch, int min_groups) {
+  int n = G;
+  while (n > 1 && (batch + n - 1) / n < min_groups) n /= 2;
+  return n;
+}
+
 // Into how many parts (a power of two, at most one per row) pcgrl_exact_diameter splits the
 // sources of a level: enough for about four thousand wavefronts.
 int exact_parts_for(int nwaves, int S) {
@@ -308,8 +361,7 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   // Levels per wavefront: all G groups when the batch alone fills the machine; fewer (the spare
   // groups then hold copies that share the observation work) when that is what it takes to have
   // about two wavefronts on each of the 1024 SIMDs (measured optimum).
-  ctx->epw = ctx->G;
-  while (ctx->epw > 1 && (cfg->batch + ctx->epw - 1) / ctx->epw < 2048) ctx->epw /= 2;
+  ctx->epw = levels_per_wave_for(ctx->G, cfg->batch, 2048);
   if (cfg->levels_per_wave > 0) {  // explicit choice, rounded down to what the size class allows
     ctx->epw = 1;
     while (ctx->epw * 2 <= cfg->levels_per_wave && ctx->epw * 2 <= ctx->G) ctx->epw *= 2;
@@ -336,31 +388,11 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
     delete ctx;
     return PCGRL_E_CONFIG;
   }
-  // Two wavefronts per level group (metrics | observation) shorten the dependent chain of a
-  // launch at the price of loading the level twice.  Measured: a gain of 10-25 % for 16x16 levels
-  // up to 2048 wavefronts and of 2-13 % beyond (observations of 1.5 KB or more per level; not where
-  // a step's observations are stored through the cache, 256-448 MB, where it costs 17 %), and of
-  // 7 % for 32x32 levels with a 12 KB observation; 4-16 % for 32x32 and 64x64 levels at batches
-  // up to 4096; a few percent either way elsewhere.
-  const size_t obs_batch_bytes = E * (size_t)cfg->batch;
-  const bool obs_cached = obs_batch_bytes > ((size_t)256 << 20) && obs_batch_bytes <= ((size_t)448 << 20) && E >= 3072;
-  ctx->split = ((ctx->S == 16 && (ctx->nwaves <= 2048 || (E >= 1536 && !obs_cached))) ||
-                (ctx->S == 32 && E >= 8192 && ctx->nwaves <= 8192) ||
-                (ctx->S >= 32 && cfg->batch <= 4096)) ? 1 : 0;
-  // A rollout split the same way (each wavefront keeps its own copy of the level for all the
-  // steps): measured -35 % per step for 16x16 levels at batches of 64 and 1024, within a few
-  // percent either way from 4096 on (100 steps per launch) except: observations under 4 KB up to a
-  // batch of 12 288 (-10...-30 %), and at every batch tried when they are 1.5 KB or more (binary16:
-  // -5...-9 % from 16 384 to 131 072); observations of 4 KB or more up to 4096 (maze16 -20 %) and
-  // from 16 384 on (-2...-3 %), but not between (8192: +6 %); -6 % for 64x64 levels; for 32x32 levels -16...-43 %
-  // at batches up to 4096; beyond, -6...-9 % for the binary problem (two diameter sweeps a step) at
-  // every batch tried and +-2 % for the dungeon.
+  // One wavefront per level group, or a metrics wavefront and observation wavefronts: by table.
+  const size_t obs_batch_bytes = ctx->obs_stride * (size_t)cfg->batch;
+  ctx->split = first_match(kStepSplit, ctx->S, cfg->batch, (int64_t)E, (int64_t)obs_batch_bytes, cfg->problem);
+  ctx->split_roll = first_match(kRolloutSplit, ctx->S, cfg->batch, (int64_t)E, (int64_t)obs_batch_bytes, cfg->problem);
   const bool obs_heavy = E >= 4096;
-  ctx->split_roll = ((ctx->S == 16 && (cfg->batch <= 2048 ||
-                                       (!obs_heavy && (cfg->batch <= 12288 || E >= 1536)) ||
-                                       (obs_heavy && (cfg->batch <= 4096 || cfg->batch >= 16384)))) ||
-                     (ctx->S == 32 && (cfg->batch <= 4096 || ctx->K == 2)) ||
-                     (ctx->S == 64 && cfg->batch <= 8192)) ? 1 : 0;
   if (cfg->split_step == PCGRL_SPLIT_OFF) ctx->split = ctx->split_roll = 0;
   if (cfg->split_step == PCGRL_SPLIT_ON) ctx->split = ctx->split_roll = 1;
   // Shape of the split step: one metrics wavefront carries as many levels as the explicit choice
@@ -375,9 +407,7 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   ctx->split_m = ctx->epw;
   if (cfg->levels_per_wave <= 0) {
     const bool large_obs = E >= 3072;
-    const int want_groups = large_obs ? 1024 : 512;
-    ctx->split_m = ctx->G;
-    while (ctx->split_m > 1 && (cfg->batch + ctx->split_m - 1) / ctx->split_m < want_groups) ctx->split_m /= 2;
+    ctx->split_m = levels_per_wave_for(ctx->G, cfg->batch, large_obs ? 1024 : 512);
     if (large_obs && ctx->split_m == 4 && (cfg->batch + 1) / 2 <= 2048) ctx->split_m = 2;
   }
   ctx->split_o = ctx->split_m;
@@ -389,8 +419,7 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   ctx->split_lds_wave = lds_for(ctx->split_o);
   // The split rollout is bound by instruction issue sooner than a single step is by its chain:
   // it packs as many levels into a wavefront as leave about a thousand workgroups (measured).
-  ctx->roll_m = ctx->G;
-  while (ctx->roll_m > 1 && (cfg->batch + ctx->roll_m - 1) / ctx->roll_m < 1024) ctx->roll_m /= 2;
+  ctx->roll_m = levels_per_wave_for(ctx->G, cfg->batch, 1024);
   // Observation wavefronts of a split rollout: one for all the levels of the metrics wavefront
   // where the observation is small, two (or one per level) where it is the larger half of the
   // work (measured on 16x16 levels: maze16 at 4096, 2.8 against 3.2 us per step; binary16 at
