@@ -279,6 +279,23 @@ int pcgrl_num_tiles(const pcgrl_ctx* ctx);
 /* Number of out-of-range actions seen since creation.  Waits for `stream`.  out: host pointer. */
 int pcgrl_bad_action_count(pcgrl_ctx* ctx, uint64_t* out, void* stream);
 
+/* The consumer's side of PCGRL_OBS_PACKED (Methods, model figure: the observation feeds the
+ * first convolution of the policy and value networks): turns bit-packed observations, as every
+ * `obs` argument of a context with obs_format = PCGRL_OBS_PACKED holds them, back into one-hot
+ * elements of the type a network wants, so that a rollout can be kept in HBM at an eighth of its
+ * size and widened only when it is read.
+ *   packed : device, uint8 [batch][pcgrl_obs_stride(ctx)], one call's worth (one slot of a rollout)
+ *   out    : device, [batch][C][obs_w][obs_w] contiguous elements of out_type (aligned to the
+ *            element size), each 0 or 1
+ *   out_type: PCGRL_UNPACK_U8 / _F16 / _BF16 / _F32
+ * Errors: E_NULL; E_CONFIG if the context's format is not packed, out_type is unknown or out is
+ * misaligned. */
+#define PCGRL_UNPACK_U8 0
+#define PCGRL_UNPACK_F16 1
+#define PCGRL_UNPACK_BF16 2
+#define PCGRL_UNPACK_F32 3
+int pcgrl_unpack_obs(const pcgrl_ctx* ctx, const uint8_t* packed, void* out, int32_t out_type, void* stream);
+
 /* Measurement aid (no passage of the paper: it is the yardstick its store-bound steps are held
  * against).  One launch that does nothing but write n_regions * region_bytes bytes to dst with
  * aligned 16-byte stores of the kind `store_mode` names (PCGRL_OBS_STORE_CACHED / _STREAM /

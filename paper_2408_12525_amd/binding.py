@@ -46,7 +46,7 @@ EXPORTS = [
     "pcgrl_metrics", "pcgrl_exact_diameter", "pcgrl_exact_diameter_static", "pcgrl_observe", "pcgrl_get_state", "pcgrl_set_state", "pcgrl_set_targets",
     "pcgrl_get_targets",
     "pcgrl_obs_shape", "pcgrl_obs_bytes", "pcgrl_obs_stride", "pcgrl_num_metrics", "pcgrl_num_tiles", "pcgrl_bad_action_count",
-    "pcgrl_selftest", "pcgrl_store_rate", "pcgrl_strerror",
+    "pcgrl_selftest", "pcgrl_store_rate", "pcgrl_unpack_obs", "pcgrl_strerror",
 ]
 
 _lib = None
@@ -99,6 +99,7 @@ def load():
     L.pcgrl_bad_action_count.argtypes = [p, C.POINTER(u64), p]
     L.pcgrl_selftest.argtypes = [C.c_int, C.POINTER(i32)]
     L.pcgrl_store_rate.argtypes = [p, C.c_int64, i32, i32, i32, p]
+    L.pcgrl_unpack_obs.argtypes = [p, p, p, i32, p]
     L.pcgrl_strerror.argtypes = [C.c_int]
     L.pcgrl_strerror.restype = C.c_char_p
     _lib = L
@@ -260,6 +261,19 @@ class Pcgrl:
     def pcgrl_exact_diameter_static(self, out, parts_log2: int = -1):
         o = self._dev(out, torch.int32, (self.B,), "out")
         _check(self.L.pcgrl_exact_diameter_static(self.h, o, parts_log2, self._st()), "pcgrl_exact_diameter_static")
+        return out
+
+    UNPACK_TYPES = {torch.uint8: 0, torch.float16: 1, torch.bfloat16: 2, torch.float32: 3}
+
+    def pcgrl_unpack_obs(self, packed, out=None, dtype=torch.uint8):
+        """Bit-packed observations [batch, stride] -> one-hot [batch, C, ow, ow] of `dtype`."""
+        pk = self._dev(packed, torch.uint8, self.obs_shape, "packed")
+        if out is None:
+            out = torch.empty(self.onehot_shape, dtype=dtype, device=self.device)
+        if out.dtype not in self.UNPACK_TYPES:
+            raise PcgrlError(f"cannot unpack into {out.dtype}")
+        o = self._dev(out, out.dtype, self.onehot_shape, "out")
+        _check(self.L.pcgrl_unpack_obs(self.h, pk, o, self.UNPACK_TYPES[out.dtype], self._st()), "pcgrl_unpack_obs")
         return out
 
     def pcgrl_observe(self, obs=None):

@@ -741,6 +741,26 @@ int pcgrl_bad_action_count(pcgrl_ctx* ctx, uint64_t* out, void* stream) {
   return PCGRL_OK;
 }
 
+int pcgrl_unpack_obs(const pcgrl_ctx* ctx, const uint8_t* packed, void* out, int32_t out_type, void* stream) {
+  if (!ctx || !packed || !out) return PCGRL_E_NULL;
+  if (ctx->cfg.obs_format != PCGRL_OBS_PACKED) return PCGRL_E_CONFIG;
+  if (out_type < PCGRL_UNPACK_U8 || out_type > PCGRL_UNPACK_F32) return PCGRL_E_CONFIG;
+  const int es = out_type == PCGRL_UNPACK_U8 ? 1 : out_type == PCGRL_UNPACK_F32 ? 4 : 2;
+  if (((uintptr_t)out & (uintptr_t)(es - 1)) != 0) return PCGRL_E_CONFIG;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return PCGRL_E_DEVICE;
+  const int32_t cells = ctx->C * ctx->cfg.obs_w * ctx->cfg.obs_w;
+  const dim3 grid((unsigned)ctx->cfg.batch), block(64);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  uint8_t* o = static_cast<uint8_t*>(out);
+  const int64_t stride = (int64_t)ctx->obs_stride;
+  if (out_type == PCGRL_UNPACK_U8) hipLaunchKernelGGL(unpack_obs_kernel<1>, grid, block, 0, st, packed, stride, o, cells, 1u);
+  else if (out_type == PCGRL_UNPACK_F16) hipLaunchKernelGGL(unpack_obs_kernel<2>, grid, block, 0, st, packed, stride, o, cells, 0x3C00u);
+  else if (out_type == PCGRL_UNPACK_BF16) hipLaunchKernelGGL(unpack_obs_kernel<2>, grid, block, 0, st, packed, stride, o, cells, 0x3F80u);
+  else hipLaunchKernelGGL(unpack_obs_kernel<4>, grid, block, 0, st, packed, stride, o, cells, 0x3F800000u);
+  return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
+}
+
 int pcgrl_store_rate(uint8_t* dst, int64_t n_regions, int32_t region_bytes, int32_t store_mode,
                      int32_t order, void* stream) {
   if (!dst) return PCGRL_E_NULL;

@@ -1774,6 +1774,64 @@ __global__ void get_targets_kernel(const uint32_t* src, int32_t* dst, int B, int
   dst[2 * idx + 1] = (int32_t)(t >> 16);
 }
 
+// The consumer's side of the bit-packed observation format: one wavefront per level turns the
+// packed row back into one-hot elements of 1, 2 or 4 bytes (the value `one`, or zero).  The
+// output of a level is written as aligned 16-byte chunks, with the few elements before the first
+// and after the last full chunk one by one; each chunk needs the 16, 8 or 4 bits that start at its
+// first cell, wherever they fall in the packed bytes.
+template <int ES>  // element size in bytes
+__global__ __launch_bounds__(64) void unpack_obs_kernel(const uint8_t* packed, int64_t packed_stride, uint8_t* out,
+                                                        int32_t cells, uint32_t one) {
+  constexpr int PER = 16 / ES;  // elements per 16-byte chunk
+  const int lane = (int)(threadIdx.x & 63u);
+  const uint8_t* row = packed + (int64_t)blockIdx.x * packed_stride;
+  uint8_t* dst = out + (int64_t)blockIdx.x * (int64_t)cells * ES;
+  // bits [e, e + PER) of the packed row (cell j is bit j % 8 of byte j / 8); reads stay inside the row
+  const int row_bytes = (cells + 7) >> 3;
+  auto bits_at = [&](int e) -> uint32_t {
+    const int b0 = e >> 3;
+    uint32_t v = row[b0];
+    if (b0 + 1 < row_bytes) v |= (uint32_t)row[b0 + 1] << 8;
+    if (b0 + 2 < row_bytes) v |= (uint32_t)row[b0 + 2] << 16;
+    return v >> (e & 7);
+  };
+  auto store_one = [&](int e) {
+    const uint32_t bit = (row[e >> 3] >> (e & 7)) & 1u;
+    if constexpr (ES == 1) dst[e] = (uint8_t)(bit ? one : 0u);
+    else if constexpr (ES == 2) reinterpret_cast<uint16_t*>(dst)[e] = (uint16_t)(bit ? one : 0u);
+    else reinterpret_cast<uint32_t*>(dst)[e] = bit ? one : 0u;
+  };
+  const int head = min(cells, (int)(((16u - (uint32_t)((uintptr_t)dst & 15u)) & 15u) / ES));  // elements before the first aligned chunk
+  const int nchunks = (cells - head) / PER;
+  const int tail0 = head + nchunks * PER;
+  if (lane < head) store_one(lane);
+  if (tail0 + lane < cells) store_one(tail0 + lane);
+  for (int c = lane; c < nchunks; c += 64) {
+    const int e = head + c * PER;
+    const uint32_t b = bits_at(e);
+    u32x4 v;
+    if constexpr (ES == 1) {
+      // a nibble times 0x204081 puts bit k at bit 8 k (0, 7, 14, 21 are shifted copies)
+      v.x = (__umul24(b & 15u, 0x00204081u) & 0x01010101u) * one;
+      v.y = (__umul24((b >> 4) & 15u, 0x00204081u) & 0x01010101u) * one;
+      v.z = (__umul24((b >> 8) & 15u, 0x00204081u) & 0x01010101u) * one;
+      v.w = (__umul24((b >> 12) & 15u, 0x00204081u) & 0x01010101u) * one;
+    } else if constexpr (ES == 2) {
+      auto two = [&](uint32_t q) { return ((q & 1u) ? one : 0u) | ((q & 2u) ? one << 16 : 0u); };
+      v.x = two(b);
+      v.y = two(b >> 2);
+      v.z = two(b >> 4);
+      v.w = two(b >> 6);
+    } else {
+      v.x = (b & 1u) ? one : 0u;
+      v.y = (b & 2u) ? one : 0u;
+      v.z = (b & 4u) ? one : 0u;
+      v.w = (b & 8u) ? one : 0u;
+    }
+    *reinterpret_cast<u32x4*>(dst + (int64_t)e * ES) = v;
+  }
+}
+
 // Measurement aid: nothing but stores, in the pattern of the observation writer (one wavefront per
 // contiguous region, aligned 16-byte stores, 1 KiB per wavefront instruction; with by_die the
 // regions are dealt to the workgroups the way a rollout deals its level groups, see

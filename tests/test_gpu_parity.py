@@ -175,6 +175,46 @@ def test_pitched_observation_layout(label, cfg, stride, split, mode):
     gpu.close()
 
 
+UNPACK = [
+    ("maze16", wl.workload("maze16", batch=37, max_steps=30, obs_format=1)),
+    ("maze64 lines", wl.workload("maze64", batch=5, max_steps=30, obs_format=1, obs_pitch=-1)),
+    ("binary32 ow63 pinpoint channel", wl.workload("binary32_rand_ow63", batch=11, max_steps=25, obs_frozen_channel=1, obs_format=1)),
+    ("dungeon32 ow15", wl.workload("dungeon32", batch=23, max_steps=30, obs_format=1, obs_pitch=240)),
+    ("binary16 ow1", wl.make_config(wl.BINARY, 40, 16, 1, max_steps=30, obs_format=1, pad_mode=wl.PAD_WALL)),
+    ("binary32 ow3", wl.workload("binary32_rand_ow3", batch=70, max_steps=30, obs_format=1)),
+]
+
+
+@pytest.mark.parametrize("label,cfg", UNPACK, ids=[c[0] for c in UNPACK])
+def test_unpack_packed_observations(label, cfg):
+    """The consumer's side of the bit-packed format: pcgrl_unpack_obs must give back the oracle's
+    one-hot cells as uint8 0/1 and as 0.0/1.0 in float16, bfloat16 and float32, also into an output
+    that starts at an odd element (its first and last few elements are then written one by one)."""
+    dev = torch.device("cuda", 0)
+    gpu, cpu = binding.Pcgrl(cfg, 0), oracle.Oracle(cfg)
+    obs = gpu.new_obs()
+    gpu.pcgrl_reset(9, obs)
+    want = cpu.reset(9)
+    acts = wl.random_actions(cfg, 10, 12)
+    for t in range(13):
+        for dt in (torch.uint8, torch.float16, torch.bfloat16, torch.float32):
+            got = gpu.pcgrl_unpack_obs(obs, dtype=dt)
+            assert got.dtype == dt and tuple(got.shape) == want.shape
+            assert torch.equal(got.cpu().to(torch.float32), torch.from_numpy(want).to(torch.float32)), (label, t, dt)
+            n = got.numel()
+            big = torch.full((n + 3,), 7, dtype=dt, device=dev)      # one element further on: misaligned chunks
+            view = big[1:n + 1].view(got.shape)
+            gpu.pcgrl_unpack_obs(obs, out=view)
+            assert torch.equal(view, got) and float(big[0]) == 7 and float(big[n + 1]) == 7, (label, t, dt)
+        if t < 12:
+            gpu.pcgrl_step(torch.from_numpy(acts[t]).to(dev), obs)
+            want = cpu.step(acts[t])[0]
+    with pytest.raises(binding.PcgrlError):
+        plain = binding.Pcgrl(dict(cfg, obs_format=0), 0)
+        plain.pcgrl_unpack_obs(plain.new_obs())
+    gpu.close()
+
+
 def test_obs_pitch_is_validated():
     for bad in (-2, 24, 4800, 100):           # unknown code, not a multiple of 16, smaller than the observation
         with pytest.raises(binding.PcgrlError):
