@@ -320,7 +320,7 @@ def summarise(run: GpuRun, step, roll):
     # which ceiling is nearer: the launch itself (an empty launch is 1.5 us), the vector ALUs, or HBM
     if launch_s < 6.0e-6 and hbm_frac < 0.05:
         bound = "launch"
-    elif valu_frac is not None and valu_frac > hbm_frac:
+    elif valu_frac is not None and valu_frac > max(hbm_frac, (traffic or 0) / launch_s / 1e9 / HBM_PEAK_GBS):
         bound = "alu"
     else:
         bound = "hbm"

@@ -99,17 +99,24 @@ int dispatch(int S, int problem, A&&... args) {
   return PCGRL_E_CONFIG;
 }
 
+// (single steps come in two builds: with and without the code that looks pinpoint cells up)
 template <int S, int PROBLEM> struct LaunchStep {
   static int run(const pcgrl_ctx* ctx, const KArgs& a, hipStream_t st) {
-    hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeStep>), dim3(ctx->nwaves), dim3(64), ctx->lds_bytes, st, a);
+    if (a.use_frozen)
+      hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeStep, true>), dim3(ctx->nwaves), dim3(64), ctx->lds_bytes, st, a);
+    else
+      hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeStep, false>), dim3(ctx->nwaves), dim3(64), ctx->lds_bytes, st, a);
     return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
   }
 };
 template <int S, int PROBLEM> struct LaunchSplit {  // a metrics wavefront and its observation wavefronts per workgroup
   static int run(const pcgrl_ctx* ctx, const KArgs& a, hipStream_t st) {
     const int obs_waves = ctx->split_m / ctx->split_o;
-    hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeSplit>), dim3(ctx->split_groups), dim3(64 * (1 + obs_waves)),
-                       obs_waves * ctx->split_lds_wave, st, a);
+    const dim3 grid(ctx->split_groups), block(64 * (1 + obs_waves));
+    if (a.use_frozen)
+      hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeSplit, true>), grid, block, obs_waves * ctx->split_lds_wave, st, a);
+    else
+      hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeSplit, false>), grid, block, obs_waves * ctx->split_lds_wave, st, a);
     return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
   }
 };
