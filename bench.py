@@ -280,16 +280,18 @@ class GpuRun:
 def store_rates(torch, binding, region_bytes, total=6 << 30):
     """What the memory system takes as a pure write stream, from the library's store-only kernel
     over a buffer far beyond the caches: one sweep over the whole buffer, and one wavefront per
-    contiguous region of about one observation (the pattern of the observation stores; with
-    non-temporal stores in workgroup order, as a step launch issues them, and with ordinary stores
-    and consecutive regions on the same die, as a rollout does)."""
+    contiguous region of what one level's observation takes in the layout the benchmark uses (the
+    pattern of the observation stores): with non-temporal stores in workgroup order, as a step
+    launch with a slot per step issues them, and the way a large rollout stores (the same for
+    whole lines per level; ordinary stores with consecutive regions on one die for dense ones)."""
     dev = torch.device("cuda", 0)
     buf = torch.empty(total, dtype=torch.uint8, device=dev)
     out = {}
     region = max(16, (region_bytes + 15) // 16 * 16)
-    for key, rb, order, mode in (("linear_fill", 64 << 10, 1, 2),
+    lines = region % 128 == 0
+    for key, rb, order, mode in (("linear_fill", 1 << 10, 1, 3),
                                  ("region_stores_step", region, 0, 2),
-                                 ("region_stores_rollout", region, 2, 1)):
+                                 ("region_stores_rollout", region, 0 if lines else 2, 2 if lines else 1)):
         n = total // rb
         binding.pcgrl_store_rate(buf, n, rb, mode, order)
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -412,7 +414,7 @@ def main():
 
     attain = None
     if not args.no_table:
-        attain = store_rates(torch, binding, head.obs_env_bytes)
+        attain = store_rates(torch, binding, head.obs_stride)
     ms_per_step = step["wall_ms_per_step"]
     out = {
         "metric": "env-steps/sec (edit+metrics+reward+obs) at 1 GPU; % of HBM roofline",

@@ -312,3 +312,39 @@ def test_pinpoint_channel_shows_exactly_the_frozen_cells_in_view():
             assert (obs[b, :5] == numpy_window(st["tiles"][b], h, w, py, px, 9, 4, True)).all()
         if t < len(acts):
             obs, _, _ = env.step(acts[t])
+
+
+def test_two_pass_estimate_depends_only_on_the_first_cells_component():
+    """The fact the GPU path's shortcut for the binary problem rests on, checked on the oracle
+    alone: flipping a cell that neither lies in the component of the first walkable cell nor
+    touches it, and does not become a walkable cell in front of that first cell, leaves the
+    two-pass estimate as it is -- on every cell of random maps, with the oracle's own BFS giving
+    the component."""
+    rng = np.random.default_rng(11)
+    checked = kept = 0
+    for trial in range(120):
+        h, w = rng.integers(3, 9, size=2)
+        tiles = (rng.random((h, w)) < rng.choice([0.35, 0.5, 0.65])).astype(np.int8)
+        before = oracle.diameter_two_pass(tiles)
+        walk = np.argwhere(tiles == 0)
+        if len(walk):
+            x = tuple(walk[0])                                   # first walkable cell, row-major
+            comp = oracle.bfs(tiles, src_index=x[0] * w + x[1]) >= 0
+        else:
+            x, comp = None, np.zeros((h, w), bool)
+        near = np.zeros((h + 2, w + 2), bool)                      # the component and its 4-neighbours
+        for dy, dx in ((0, 0), (1, 0), (-1, 0), (0, 1), (0, -1)):
+            near[1 + dy:1 + dy + h, 1 + dx:1 + dx + w] |= comp
+        near = near[1:-1, 1:-1]
+        for cy in range(h):
+            for cx in range(w):
+                opens = tiles[cy, cx] == 1                         # wall -> empty
+                in_front = x is None or (cy, cx) < x
+                flipped = tiles.copy()
+                flipped[cy, cx] ^= 1
+                after = oracle.diameter_two_pass(flipped)
+                checked += 1
+                if not near[cy, cx] and not (opens and in_front):
+                    assert after == before, (trial, cy, cx, tiles)
+                    kept += 1
+    assert kept > checked // 4          # the shortcut applies to a good share of the edits
