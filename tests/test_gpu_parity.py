@@ -710,11 +710,11 @@ def _rollout_against_oracle(cfg, T, slots, seed):
     want = {}
     for t in range(T):
         o, r, d = cpu.step(acts_np[t])
-        want[t % slots] = expected_obs(cfg, o)
+        want[t % slots] = o
         assert np.array_equal(rew[t].cpu().numpy(), r), f"reward step {t}"
         assert np.array_equal(done[t].cpu().numpy(), d), f"done step {t}"
     for k, o in want.items():
-        assert_same("obs", obs[k], o, f"slot {k}")
+        check_obs(roll, obs[k], o, f"slot {k}")
     assert_same("metrics", roll.pcgrl_metrics(), cpu.metrics(), "after rollout")
     compare_state(roll, cpu, "after rollout")
     roll.close()
@@ -749,6 +749,72 @@ def test_random_configurations_and_launch_shapes():
         run_parity(cfg, steps, seed=int(rng.integers(1, 1000)), aseed=int(rng.integers(1, 1000)),
                    bad_fraction=0.02, state_every=steps, label=f"random configuration {n}")
         _rollout_against_oracle(cfg, steps, int(rng.choice([1, 2, steps])), int(rng.integers(1, 1000)))
+
+
+def test_random_configurations_with_pitched_observations():
+    """The same kind of draws with an observation pitch on top: whole lines, or a random multiple of
+    16 bytes at or above the observation's size; steps and a rollout against the oracle."""
+    rng = np.random.default_rng(17)
+    for n in range(24):
+        problem = int(rng.integers(0, 3))
+        size = int(rng.choice([7, 16, 16, 29, 32, 64]))
+        ow = int(rng.choice([1, 3, 8, 15, 31, 40, 63]))
+        batch = int(rng.choice([2, 37, 130, 1000, 2049, 4100]))
+        if size > 32:
+            batch = min(batch, 1000)
+        packed = int(rng.choice([0, 0, 1]))
+        fzc = int(rng.integers(0, 2))
+        pad = int(rng.integers(0, 2))
+        C = wl.NUM_TILES[problem] + (1 - pad) + fzc
+        cells = C * ow * ow
+        nbytes = (cells + 7) // 8 if packed else cells
+        pitch = -1 if rng.random() < 0.5 else (nbytes + 15) // 16 * 16 + 16 * int(rng.integers(0, 9))
+        cfg = wl.make_config(
+            problem, batch, size, ow, min_size=int(rng.integers(1, size + 1)) if rng.random() < 0.5 else None,
+            pad_mode=pad, pos_mode=int(rng.integers(0, 2)), n_frozen=int(rng.choice([0, 0, 1])),
+            max_steps=int(rng.choice([9, 1000])), autoreset=int(rng.integers(0, 2)),
+            levels_per_wave=int(rng.choice([0, 0, 1, 2, 4])), split_step=int(rng.choice([0, 1, 2])),
+            obs_store_mode=int(rng.choice([0, 1, 2, 3])), obs_format=packed, obs_frozen_channel=fzc,
+            split_obs_levels=int(rng.choice([0, 0, 1, 2])), obs_pitch=pitch)
+        steps = 16 if batch * size * size < 3e6 else 8
+        run_parity(cfg, steps, seed=int(rng.integers(1, 1000)), aseed=int(rng.integers(1, 1000)),
+                   state_every=steps, label=f"random pitched configuration {n} (pitch {pitch}, {nbytes} bytes)")
+        _rollout_against_oracle(cfg, steps, int(rng.choice([1, 2, steps])), int(rng.integers(1, 1000)))
+
+
+def test_pinpoints_installed_later_are_respected():
+    """A context created without pinpoints runs the step kernels that carry no pinpoint code; once
+    pcgrl_set_state installs a frozen mask, steps (and a rollout) must leave those cells alone."""
+    dev = torch.device("cuda", 0)
+    for name, batch, split in (("maze16", 50, 2), ("maze64", 5, 1), ("dungeon32", 20, 1)):
+        cfg = wl.workload(name, batch=batch, max_steps=10**6, autoreset=0, split_step=split)
+        gpu, cpu = binding.Pcgrl(cfg, 0), oracle.Oracle(cfg)
+        obs = gpu.new_obs()
+        rew = torch.empty(batch, dtype=torch.float32, device=dev)
+        gpu.pcgrl_reset(4, obs)
+        cpu.reset(4)
+        acts = wl.random_actions(cfg, 5, 60)
+        for t in range(10):                                        # steps before any pinpoint exists
+            gpu.pcgrl_step(torch.from_numpy(acts[t]).to(dev), obs, rew)
+            o, r, _ = cpu.step(acts[t])
+            assert_same("obs", obs, o, f"{name} step {t}")
+        st = cpu.get_state()
+        rng = np.random.default_rng(3)
+        fro = (rng.random(st["tiles"].shape) < 0.4).astype(np.uint8)
+        gpu.pcgrl_set_state(*(torch.from_numpy(a).to(dev) for a in (st["tiles"], fro, st["hw"], st["pos"])))
+        cpu.set_state(st["tiles"], fro, st["hw"], st["pos"])
+        for t in range(10, 40):
+            gpu.pcgrl_step(torch.from_numpy(acts[t]).to(dev), obs, rew)
+            o, r, _ = cpu.step(acts[t])
+            assert_same("obs", obs, o, f"{name} step {t}")
+            assert np.array_equal(rew.cpu().numpy(), r), f"{name} step {t}"
+        compare_state(gpu, cpu, f"{name} after frozen steps")
+        gpu.pcgrl_rollout(torch.from_numpy(acts[40:]).to(dev))
+        for t in range(40, 60):
+            cpu.step(acts[t], want_obs=False)
+        compare_state(gpu, cpu, f"{name} after the rollout")
+        assert (cpu.get_state()["tiles"][fro.astype(bool)] == st["tiles"][fro.astype(bool)]).all()
+        gpu.close()
 
 
 def test_small_buffers_and_every_window_size():
