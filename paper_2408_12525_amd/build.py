@@ -17,6 +17,9 @@ HIPCC_FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     # the reward is a sum of float32 products in a fixed order: no fused multiply-adds
     "-ffp-contract=off",
+    # leading scalar kernel arguments (up to 8 of them, 14 dwords) are preloaded into scalar
+    # registers at wavefront launch; the step kernel is written for that
+    "-mllvm", "-amdgpu-kernarg-preload-count=8",
 ]
 
 

@@ -99,13 +99,21 @@ int dispatch(int S, int problem, A&&... args) {
   return PCGRL_E_CONFIG;
 }
 
+// The step kernel takes what it needs first as leading scalar arguments (see the kernel).
+inline uint32_t step_shape(const KArgs& a) {
+  return (uint32_t)a.B | ((uint32_t)(a.envs_per_wave_log2 & 0xff) << 25) |
+         ((uint32_t)((a.envs_per_wave_log2 >> 8) & 0xff) << 27) | ((uint32_t)(a.use_frozen & 3) << 29);
+}
+#define PCGRL_STEP_ARGS(a) (a).planes, (a).frozen, (a).env, (a).metrics, (a).targets, (a).actions, step_shape(a), (a).plane_stride, (a)
 // (single steps come in two builds: with and without the code that looks pinpoint cells up)
 template <int S, int PROBLEM> struct LaunchStep {
   static int run(const pcgrl_ctx* ctx, const KArgs& a, hipStream_t st) {
     if (a.use_frozen)
-      hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeStep, true>), dim3(ctx->nwaves), dim3(64), ctx->lds_bytes, st, a);
+      hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeStep, true>), dim3(ctx->nwaves), dim3(64), ctx->lds_bytes, st,
+                         PCGRL_STEP_ARGS(a));
     else
-      hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeStep, false>), dim3(ctx->nwaves), dim3(64), ctx->lds_bytes, st, a);
+      hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeStep, false>), dim3(ctx->nwaves), dim3(64), ctx->lds_bytes, st,
+                         PCGRL_STEP_ARGS(a));
     return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
   }
 };
@@ -114,23 +122,25 @@ template <int S, int PROBLEM> struct LaunchSplit {  // a metrics wavefront and i
     const int obs_waves = ctx->split_m / ctx->split_o;
     const dim3 grid(ctx->split_groups), block(64 * (1 + obs_waves));
     if (a.use_frozen)
-      hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeSplit, true>), grid, block, obs_waves * ctx->split_lds_wave, st, a);
+      hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeSplit, true>), grid, block, obs_waves * ctx->split_lds_wave, st,
+                         PCGRL_STEP_ARGS(a));
     else
-      hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeSplit, false>), grid, block, obs_waves * ctx->split_lds_wave, st, a);
+      hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeSplit, false>), grid, block, obs_waves * ctx->split_lds_wave, st,
+                         PCGRL_STEP_ARGS(a));
     return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
   }
 };
 template <int S, int PROBLEM> struct LaunchRolloutSplit {
   static int run(const pcgrl_ctx* ctx, const KArgs& a, hipStream_t st) {
     const int obs_waves = ctx->roll_m / ctx->roll_o;
-    hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeRolloutSplit>), dim3(ctx->roll_groups),
+    hipLaunchKernelGGL((rollout_kernel<S, PROBLEM, kModeRolloutSplit>), dim3(ctx->roll_groups),
                        dim3(64 * (1 + obs_waves)), obs_waves * ctx->roll_lds_wave, st, a);
     return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
   }
 };
 template <int S, int PROBLEM> struct LaunchRollout {
   static int run(const pcgrl_ctx* ctx, const KArgs& a, hipStream_t st) {
-    hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeRollout>), dim3(ctx->nwaves), dim3(64), ctx->lds_bytes, st, a);
+    hipLaunchKernelGGL((rollout_kernel<S, PROBLEM, kModeRollout>), dim3(ctx->nwaves), dim3(64), ctx->lds_bytes, st, a);
     return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
   }
 };

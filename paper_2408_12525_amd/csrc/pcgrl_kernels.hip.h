@@ -80,15 +80,37 @@ struct KArgs {
   int32_t ctrl_lo[kMaxMetrics], ctrl_hi[kMaxMetrics];
 };
 
-// The calling kernel's argument block (KArgs is the first parameter of every kernel here) read
+// The step kernel's argument block read
 // through a pointer the optimiser cannot trace back to the arguments.  Blocks that run once in
 // thousands of steps (a level restarting) read their configuration through it: loads made this way
 // stay inside the block, whereas loads from the by-value argument are hoisted, with all the scalar
 // arithmetic that depends on them, to the top of the kernel where every wavefront pays for them.
-__device__ __forceinline__ const KArgs& cold_args() {
+// fill_rest_of_args() below reads the whole block this way at a point of the caller's choosing.
+// (In the single-step kernel the block comes after the arguments that are handed over in
+// registers, in the rollout kernel it is the only argument: ROLL says which kernel is running.)
+constexpr int kStepArgsOffset = 56;
+template <bool ROLL> __device__ __forceinline__ const KArgs& cold_args() {
   auto seg = __builtin_amdgcn_kernarg_segment_ptr();
   asm volatile("" : "+s"(seg));
-  return *(const KArgs*)seg;
+  return *(const KArgs*)((const char*)seg + (ROLL ? 0 : kStepArgsOffset));
+}
+
+// Completes an argument block of which only the fields that came in registers are set (`hot`:
+// the six state pointers, B, plane_stride, envs_per_wave_log2, use_frozen) with everything else
+// from the block in memory.  The fetch, and the wait for it, stay where this is called.
+__device__ __forceinline__ void fill_rest_of_args(KArgs& hot) {
+  KArgs t = cold_args<false>();
+  t.planes = hot.planes;
+  t.frozen = hot.frozen;
+  t.env = hot.env;
+  t.metrics = hot.metrics;
+  t.targets = hot.targets;
+  t.actions = hot.actions;
+  t.B = hot.B;
+  t.plane_stride = hot.plane_stride;
+  t.envs_per_wave_log2 = hot.envs_per_wave_log2;
+  t.use_frozen = hot.use_frozen;
+  hot = t;
 }
 
 template <int S> struct RowWord { using T = uint32_t; };
@@ -1129,7 +1151,8 @@ __global__ void max_over_parts_kernel(const int32_t* partial, int32_t* out, int 
 // barrier, which this wavefront enters only when its loads have returned, keeps that wavefront
 // from storing the new state before.
 template <int S, int PROBLEM, bool PIN>
-__device__ __forceinline__ void obs_wave_step(const KArgs& a, const Lanes<S>& L, const WaveMap<S>& wm) {
+__device__ __forceinline__ void obs_wave_step(KArgs& a, const Lanes<S>& L, WaveMap<S>& wm, uint32_t* lds_all, int wid) {
+  // (on entry `a` holds only what came in registers; the rest is fetched once the loads are issued)
   using W = typename RowWord<S>::T;
   using PR = Prob<PROBLEM>;
   if (wm.env0 >= a.B) {  // the batch ends inside this workgroup: only the barrier is owed
@@ -1150,6 +1173,8 @@ __device__ __forceinline__ void obs_wave_step(const KArgs& a, const Lanes<S>& L,
   // where the observation goes is worked out, and its staging words are cleared, while the loads
   // are in flight (fenced off so that no use of a loaded value, with its wait, moves in between)
   __builtin_amdgcn_sched_barrier(0);
+  fill_rest_of_args(a);
+  wm.lds = lds_all + (wid - 1) * a.obs_lds_words;
   ObsPlan pl = obs_plan(a, L.lane, wm.sl, a.obs, wm.env0, wm.nvalid);
   obs_plan_pin(pl);
   obs_clear(wm.lds, L.lane, pl);
@@ -1198,7 +1223,7 @@ __device__ __forceinline__ void obs_wave_step(const KArgs& a, const Lanes<S>& L,
   }
   const bool restart = wm.valid && done && a.autoreset != 0;
   if (wave_any<S>(restart)) {  // the observation then shows the first state of the next episode
-    const KArgs& ra = cold_args();
+    const KArgs& ra = cold_args<false>();
     W np[PR::P], nfz;
     int nh, nw, npy, npx;
     uint64_t nkey = env_key(ra.seed, (uint64_t)wm.envl, (uint64_t)((int)er0.w + 1));
@@ -1285,7 +1310,7 @@ __device__ __forceinline__ void obs_wave_rollout(const KArgs& a, const Lanes<S>&
     }
     const bool restart = wm.valid && done && a.autoreset != 0;
     if (wave_any<S>(restart)) {
-      const KArgs& ra = cold_args();
+      const KArgs& ra = cold_args<true>();
       W np[PR::P], nfz;
       int nh, nw, npy, npx;
       uint64_t nkey = env_key(ra.seed, (uint64_t)wm.envl, (uint64_t)(episode + 1));
@@ -1315,34 +1340,22 @@ __device__ __forceinline__ void obs_wave_rollout(const KArgs& a, const Lanes<S>&
   }
 }
 
-// One environment step of every level (pcgrl_step), or, with ROLL, `rollout_steps` consecutive
-// steps (pcgrl_rollout) during which the levels never leave the registers: per step only the
-// action is read and the observation, reward and done flag are written.
-// PIN = false is the same kernel for contexts none of whose levels has a pinpoint cell
-// (use_frozen == 0; single steps only): the code that looks pinpoints up is left out, which frees
-// enough registers for one more wavefront per SIMD on 64-row levels (67 -> 62 VGPRs: all 8192
-// wavefronts of the 64x64 maze at a batch of 8192 resident at once, -2.3 % per step; 32x32 dungeon
-// -2.8 %).
-template <int S, int PROBLEM, int MODE, bool PIN = true>
-__global__ __launch_bounds__(MODE == kModeSplit || MODE == kModeRolloutSplit ? 320 : 64) void step_kernel(KArgs a) {
+// The body of the two kernels below.  On entry `a` holds what a step needs to request its loads
+// (the six state pointers, B, plane_stride, envs_per_wave_log2, use_frozen); a rollout has all of it.
+// PIN = false is the same code for contexts none of whose levels has a pinpoint cell
+// (use_frozen == 0; single steps only): what looks pinpoints up is left out, which frees enough
+// registers for one more wavefront per SIMD on 64-row levels (all 8192 wavefronts of the 64x64
+// maze at a batch of 8192 resident at once, -2.3 % per step; 32x32 dungeon -2.8 %).
+template <int S, int PROBLEM, int MODE, bool PIN>
+__device__ __forceinline__ void step_body(KArgs& a) {
   using W = typename RowWord<S>::T;
   using PR = Prob<PROBLEM>;
   constexpr bool ROLL = MODE == kModeRollout || MODE == kModeRolloutSplit;
   constexpr bool SPLIT = MODE == kModeSplit || MODE == kModeRolloutSplit;
   extern __shared__ uint32_t lds_all[];
-  // fetch the head of the argument block in one go; the rest arrives while the loads are in flight
-  if constexpr (!SPLIT)
-    asm volatile("" ::"s"(a.planes), "s"(a.frozen), "s"(a.env), "s"(a.metrics), "s"(a.targets),
-                 "s"(a.actions), "s"(a.B), "s"(a.plane_stride), "s"(a.envs_per_wave_log2), "s"(a.use_frozen));
-  else  // (the split kernel's wavefronts are lean enough to hold what the observation path reads, too)
-    asm volatile("" ::"s"(a.planes), "s"(a.frozen), "s"(a.env), "s"(a.metrics), "s"(a.targets),
-                 "s"(a.actions), "s"(a.B), "s"(a.plane_stride), "s"(a.envs_per_wave_log2), "s"(a.use_frozen),
-                 "s"(a.obs), "s"(a.env_obs_bytes), "s"(a.obs_packed), "s"(a.obs_w), "s"(a.obs_lds_words),
-                 "s"(a.max_steps), "s"(a.max_changes), "s"(a.pos_mode), "s"(a.autoreset), "s"(a.pad_mode),
-                 "s"(a.obs_frozen_channel), "s"(a.stream_obs));
   Lanes<S> L;
   WaveMap<S> wm;
-  wm.init(a, L, lds_all, level_group_of_block<ROLL>(a.by_die), a.envs_per_wave_log2 & 0xff);
+  wm.init(a, L, lds_all, level_group_of_block<ROLL>(ROLL ? a.by_die : 0), a.envs_per_wave_log2 & 0xff);
   // SPLIT: the workgroup is two wavefronts on the same levels; wavefront 0 does the metrics, the
   // reward and the state stores (the code below, without its observation parts), wavefront 1 the
   // observation; both load the same (old) state
@@ -1352,9 +1365,13 @@ __global__ __launch_bounds__(MODE == kModeSplit || MODE == kModeRolloutSplit ? 3
     const int wid = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     if (wid != 0) {
       const int lg = a.envs_per_wave_log2 & 0xff, lgo = (a.envs_per_wave_log2 >> 8) & 0xff;
-      wm.init(a, L, lds_all + (wid - 1) * a.obs_lds_words, (level_group_of_block<ROLL>(a.by_die) << (lg - lgo)) + wid - 1, lgo);
-      if constexpr (ROLL) obs_wave_rollout<S, PROBLEM>(a, L, wm);
-      else obs_wave_step<S, PROBLEM, PIN>(a, L, wm);
+      wm.init(a, L, nullptr, (level_group_of_block<ROLL>(ROLL ? a.by_die : 0) << (lg - lgo)) + wid - 1, lgo);
+      if constexpr (ROLL) {
+        wm.lds = lds_all + (wid - 1) * a.obs_lds_words;
+        obs_wave_rollout<S, PROBLEM>(a, L, wm);
+      } else {
+        obs_wave_step<S, PROBLEM, PIN>(a, L, wm, lds_all, wid);
+      }
       __builtin_amdgcn_endpgm();  // (not a return: the two paths must not meet again, or the
                                   // compiler makes this one wait for the other one's loads)
     }
@@ -1389,8 +1406,10 @@ __global__ __launch_bounds__(MODE == kModeSplit || MODE == kModeRolloutSplit ? 3
   uint32_t tg_l = a.targets[mrow + yi];
   int regions_now = a.metrics[mrow];
   const float w_l = __uint_as_float((a.targets - kMaxMetrics)[yi]);  // (the row in front of the ranges)
-  // every load above is issued before anything below waits for one of them
+  // every load above is issued before anything below waits for one of them; now the rest of the
+  // arguments is fetched, in their shadow
   __builtin_amdgcn_sched_barrier(0);
+  if constexpr (!ROLL) fill_rest_of_args(a);
   // the observation wavefront has received the old state before this wavefront goes on to store
   // the new one (this wavefront passes the barrier with its own loads still in flight)
   if constexpr (SPLIT) {
@@ -1579,7 +1598,7 @@ __global__ __launch_bounds__(MODE == kModeSplit || MODE == kModeRolloutSplit ? 3
     }
     // ---- auto-reset: fresh seeded episode for the finished levels; the others keep their registers
     if (any_restart) {
-      const KArgs& ra = cold_args();
+      const KArgs& ra = cold_args<ROLL>();
       W np[PR::P], nfz;
       int nh, nw, npy, npx;
       uint64_t nkey = env_key(ra.seed, (uint64_t)wm.envl, (uint64_t)(er.episode + 1));
@@ -1685,6 +1704,47 @@ __global__ __launch_bounds__(MODE == kModeSplit || MODE == kModeRolloutSplit ? 3
     if (targets_dirty) a.targets[(size_t)wm.env * kMaxMetrics + L.y] = tg_l;
   }
   if constexpr (SPLIT) __builtin_amdgcn_endpgm();  // see the observation wavefront's exit above
+}
+
+// One environment step of every level (pcgrl_step).  What a step needs to request its loads -- the
+// six state pointers, the batch, the plane stride and the wave shape -- comes as leading scalar
+// arguments of 14 dwords, which the library is compiled to have preloaded into scalar registers
+// when a wavefront is launched (where the firmware cannot do that, the compiler's own prologue
+// loads them): a wavefront then computes its addresses and issues its loads at once, instead of
+// first waiting for a fetch of its argument block through caches that every launch starts with
+// empty (64x64 maze at a batch of 8192: 16.3 -> 15.8 us per step).  The rest of the configuration
+// follows as the block `rest`, which only fixes where that block lies among the arguments: it is
+// read through fill_rest_of_args() once the loads are under way.
+//   shape: batch | levels per wavefront (log2) << 25 | the same for an observation wavefront << 27
+//          | use_frozen << 29
+template <int S, int PROBLEM, int MODE, bool PIN>
+__global__ __launch_bounds__(MODE == kModeSplit ? 320 : 64) void step_kernel(
+    void* planes_, void* frozen_, EnvRec* env_, int32_t* metrics_, uint32_t* targets_, const int32_t* actions_,
+    uint32_t shape, int32_t plane_stride_, KArgs rest) {
+  static_assert(MODE == kModeStep || MODE == kModeSplit, "single steps only");
+  static_assert(alignof(KArgs) == 8 && 6 * sizeof(void*) + 8 == kStepArgsOffset, "cold_args() assumes this layout");
+  (void)rest;
+  KArgs a;
+  a.planes = planes_;
+  a.frozen = frozen_;
+  a.env = env_;
+  a.metrics = metrics_;
+  a.targets = targets_;
+  a.actions = actions_;
+  a.B = (int32_t)(shape & 0x1ffffffu);
+  a.plane_stride = plane_stride_;
+  a.envs_per_wave_log2 = (int32_t)(((shape >> 25) & 3u) | (((shape >> 27) & 3u) << 8));
+  a.use_frozen = (int32_t)((shape >> 29) & 3u);
+  step_body<S, PROBLEM, MODE, PIN>(a);
+}
+
+// `rollout_steps` consecutive steps per launch (pcgrl_rollout), during which the levels never
+// leave the registers: per step only the action is read and the observation, reward and done
+// flag are written.  A launch per hundred steps has nothing to gain from preloaded arguments.
+template <int S, int PROBLEM, int MODE>
+__global__ __launch_bounds__(MODE == kModeRolloutSplit ? 320 : 64) void rollout_kernel(KArgs a) {
+  static_assert(MODE == kModeRollout || MODE == kModeRolloutSplit, "rollouts only");
+  step_body<S, PROBLEM, MODE, true>(a);
 }
 
 // ------------------------------------------------- plain-layout conversion
