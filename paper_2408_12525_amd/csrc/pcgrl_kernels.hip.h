@@ -1274,7 +1274,15 @@ __device__ __forceinline__ void obs_wave_rollout(const KArgs& a, const Lanes<S>&
   uint64_t key = (uint64_t)er1.x | ((uint64_t)er1.y << 32);
   W inside = inside_row<W>(L.y, h, w);
   const int nsteps = a.rollout_steps;
+  // Where an observation goes depends on its slot only through the slot's address modulo 16: with
+  // slots a multiple of 16 bytes apart (any batch that is a multiple of 16, any layout padded to
+  // cache lines) the plan is worked out once and only its base address moves from step to step.
+  const size_t slot_bytes = (size_t)a.B * (size_t)a.env_obs_bytes;
+  const bool fixed_plan = (slot_bytes & 15u) == 0;
+  ObsPlan pl = obs_plan(a, L.lane, wm.sl, a.obs, wm.env0, wm.nvalid);
+  uint8_t* const base0 = pl.base;
   int slot = 0;
+  size_t slot_off = 0;
   for (int step = 0; step < nsteps; ++step) {
     int act_next = -1;
     if (step + 1 < nsteps) act_next = a.actions[(size_t)(step + 1) * a.B + wm.envl];
@@ -1330,10 +1338,11 @@ __device__ __forceinline__ void obs_wave_rollout(const KArgs& a, const Lanes<S>&
         n_changes = 0;
       }
     }
-    uint8_t* obs = a.obs + (size_t)slot * (size_t)a.B * (size_t)a.env_obs_bytes;
+    if (fixed_plan) pl.base = base0 + slot_off;
+    else pl = obs_plan(a, L.lane, wm.sl, a.obs + slot_off, wm.env0, wm.nvalid);
     slot = slot + 1 == a.obs_slots ? 0 : slot + 1;  // (step t writes slot t mod obs_slots)
-    observe<S, PROBLEM, false, true>(a, L, wm, obs_plan(a, L.lane, wm.sl, obs, wm.env0, wm.nvalid), p, fz, inside, qy,
-                                     qx);
+    slot_off = slot == 0 ? 0 : slot_off + slot_bytes;
+    observe<S, PROBLEM, false, true>(a, L, wm, pl, p, fz, inside, qy, qx);
     py = qy;
     px = qx;
     act = act_next;
@@ -1440,7 +1449,21 @@ __device__ __forceinline__ void step_body(KArgs& a) {
   uint32_t next_cell_frozen = 0;
 
   const int nsteps = ROLL ? a.rollout_steps : 1;
+  // (a rollout that writes its own observations: the plan of slot 0 serves every slot whose
+  // address differs from it by a multiple of 16 bytes, see obs_wave_rollout)
   [[maybe_unused]] int slot = 0;
+  [[maybe_unused]] size_t slot_off = 0;
+  [[maybe_unused]] size_t slot_bytes = 0;
+  [[maybe_unused]] bool fixed_plan = false;
+  [[maybe_unused]] uint8_t* base0 = nullptr;
+  if constexpr (ROLL && !SPLIT) {
+    if (a.obs != nullptr) {
+      slot_bytes = (size_t)a.B * (size_t)a.env_obs_bytes;
+      fixed_plan = (slot_bytes & 15u) == 0;
+      pl = obs_plan(a, L.lane, wm.sl, a.obs, wm.env0, wm.nvalid);
+      base0 = pl.base;
+    }
+  }
   for (int step = 0; step < nsteps; ++step) {
     // the next step's action is requested now and used one iteration later
     int act_next = -1;
@@ -1450,9 +1473,10 @@ __device__ __forceinline__ void step_body(KArgs& a) {
     uint8_t* obs = a.obs;
     if constexpr (ROLL && !SPLIT) {
       if (obs != nullptr) {
-        obs += (size_t)slot * (size_t)a.B * (size_t)a.env_obs_bytes;
+        if (fixed_plan) pl.base = base0 + slot_off;
+        else pl = obs_plan(a, L.lane, wm.sl, obs + slot_off, wm.env0, wm.nvalid);
         slot = slot + 1 == a.obs_slots ? 0 : slot + 1;  // (step t writes slot t mod obs_slots)
-        pl = obs_plan(a, L.lane, wm.sl, obs, wm.env0, wm.nvalid);
+        slot_off = slot == 0 ? 0 : slot_off + slot_bytes;
       }
     }
 
