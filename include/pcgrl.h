@@ -139,6 +139,12 @@ typedef struct {
                            lines are written by one wavefront only reach memory about half as fast
                            again).  The bytes between two observations are written as zeros.  The
                            caller sees [batch][pitch] bytes, e.g. as a strided [batch][C][ow][ow] view */
+  int32_t rollout_turns; /* tuning only, results do not depend on it: 0 = automatic; 1, 2 or 4 = how
+                           many observation wavefronts take the steps of a pcgrl_rollout in turn
+                           (each keeps its own copy of the levels and writes the observation of
+                           every n-th step).  Pays where the batch leaves most of the chip idle:
+                           the automatic choice takes turns only while every wavefront still has
+                           a SIMD to itself; a workgroup holds at most four observation wavefronts */
 } pcgrl_config;
 
 #define PCGRL_OBS_PITCH_LINES (-1)

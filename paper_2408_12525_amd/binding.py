@@ -38,6 +38,7 @@ class PcgrlConfig(C.Structure):
         ("obs_frozen_channel", C.c_int32),
         ("split_obs_levels", C.c_int32),
         ("obs_pitch", C.c_int32),
+        ("rollout_turns", C.c_int32),
     ]
 
 

@@ -21,7 +21,7 @@ struct pcgrl_ctx {
   size_t word_bytes;
   size_t lds_bytes;  // per wavefront
   int split_roll;    // pcgrl_rollout with observations does the same, with its own shape:
-  int roll_m, roll_o, roll_groups;
+  int roll_m, roll_o, roll_groups, roll_turns;
   size_t roll_lds_wave;
   int split;         // pcgrl_step with an observation uses the metrics | observation kernel, with
   int split_m, split_o, split_groups;  // this many levels per metrics / observation wavefront and workgroups
@@ -76,6 +76,7 @@ int check_config(const pcgrl_config* c) {
   if (c->obs_store_mode < 0 || c->obs_store_mode > 3) return PCGRL_E_CONFIG;
   if (c->split_step < 0 || c->split_step > 2) return PCGRL_E_CONFIG;
   if (c->split_obs_levels < 0 || c->split_obs_levels > 4) return PCGRL_E_CONFIG;
+  if (c->rollout_turns != 0 && c->rollout_turns != 1 && c->rollout_turns != 2 && c->rollout_turns != 4) return PCGRL_E_CONFIG;
   if (c->obs_format != PCGRL_OBS_ONEHOT_U8 && c->obs_format != PCGRL_OBS_PACKED) return PCGRL_E_CONFIG;
   if (c->obs_pitch < PCGRL_OBS_PITCH_LINES || (c->obs_pitch > 0 && (c->obs_pitch & 15) != 0)) return PCGRL_E_CONFIG;
   for (int j = 0; j < 8; ++j)
@@ -132,7 +133,7 @@ template <int S, int PROBLEM> struct LaunchSplit {  // a metrics wavefront and i
 };
 template <int S, int PROBLEM> struct LaunchRolloutSplit {
   static int run(const pcgrl_ctx* ctx, const KArgs& a, hipStream_t st) {
-    const int obs_waves = ctx->roll_m / ctx->roll_o;
+    const int obs_waves = (ctx->roll_m / ctx->roll_o) << ((a.envs_per_wave_log2 >> 16) & 0xff);
     hipLaunchKernelGGL((rollout_kernel<S, PROBLEM, kModeRolloutSplit>), dim3(ctx->roll_groups),
                        dim3(64 * (1 + obs_waves)), obs_waves * ctx->roll_lds_wave, st, a);
     return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
@@ -448,6 +449,30 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   ctx->roll_groups = (cfg->batch + ctx->roll_m - 1) / ctx->roll_m;
   ctx->roll_lds_wave = lds_for(ctx->roll_o);
   if (ctx->roll_lds_wave * (ctx->roll_m / ctx->roll_o) > 64 * 1024) ctx->split_roll = 0;
+  // A small batch leaves most SIMDs idle while every wavefront runs one long dependent chain per
+  // step.  The observation wavefronts then take the steps in turn: each follows the level through
+  // all the edits (a few dozen instructions a step) and builds the observation of every n-th step
+  // only.  As many turns (1, 2, 4) as keep the launch at two wavefronts per SIMD (2048 in all;
+  // three where the observation is the longer half of the work) and a workgroup at four
+  // observation wavefronts.  Measured, us per step with 1 / 2 / 4 turns: 16x16 maze at a batch of
+  // 64 1.46 / 0.95 / 0.92, at 512 1.59 / 1.09 / 1.26, at 1024 1.80 / 1.47 / 2.31, at 2048 2.29 /
+  // 2.95 / 2.97; 64x64 maze at 64 1.42 / 1.26 / 1.24; 32x32 dungeon at 512 1.58 / 1.50 / 1.47, at
+  // 1024 1.55 / 1.61 / 2.66; 16x16 binary at 64 1.21 / 1.18 / 1.16 (its metrics wavefront is the
+  // longer one).
+  {
+    const int per_step = ctx->roll_m / ctx->roll_o;
+    auto fits = [&](int turns) {
+      return per_step * turns <= 4 && ctx->roll_lds_wave * per_step * turns <= 64 * 1024;
+    };
+    const long long most_waves = obs_heavy ? 3072 : 2048;
+    ctx->roll_turns = 1;
+    if (cfg->rollout_turns > 0) {
+      while (ctx->roll_turns * 2 <= cfg->rollout_turns && fits(ctx->roll_turns * 2)) ctx->roll_turns *= 2;
+    } else {
+      while (fits(ctx->roll_turns * 2) && (long long)ctx->roll_groups * (1 + per_step * ctx->roll_turns * 2) <= most_waves)
+        ctx->roll_turns *= 2;
+    }
+  }
 
   ctx->exact_parts_log2 = exact_parts_for(ctx->nwaves, ctx->S);
   const size_t rows = (size_t)ctx->B_pad * ctx->S;
@@ -626,7 +651,12 @@ int pcgrl_rollout(pcgrl_ctx* ctx, const int32_t* actions, int32_t n_steps, uint8
   a.by_die = (a.stream_obs == kStoreCached && (ctx->obs_stride & 127) != 0) ? 1 : 0;
   if (obs && ctx->split_roll) {
     auto lg2 = [](int v) { return v == 4 ? 2 : v == 2 ? 1 : 0; };
-    a.envs_per_wave_log2 = lg2(ctx->roll_m) | (lg2(ctx->roll_o) << 8);
+    // Wavefronts that take turns are not ordered among each other: a slot that is written more than
+    // once in this rollout must be written by the same wavefront every time, i.e. the number of
+    // turns has to divide the number of slots.
+    int turns = ctx->roll_turns;
+    while (turns > 1 && a.obs_slots != n_steps && a.obs_slots % turns != 0) turns /= 2;
+    a.envs_per_wave_log2 = lg2(ctx->roll_m) | (lg2(ctx->roll_o) << 8) | (lg2(turns) << 16);
     a.obs_lds_words = (int32_t)(ctx->roll_lds_wave / 4);
     return dispatch<LaunchRolloutSplit>(ctx->S, ctx->cfg.problem, ctx, a, static_cast<hipStream_t>(stream));
   }

@@ -55,7 +55,9 @@ struct KArgs {
   const int32_t* actions;
   int32_t B, plane_stride;
   int32_t envs_per_wave_log2;  // bits 0-7: log2 of the distinct levels per wavefront (at most 64 / S);
-                               // bits 8-15, split step only: the same for an observation wavefront
+                               // bits 8-15, split step only: the same for an observation wavefront;
+                               // bits 16-23, split rollout only: log2 of the observation wavefronts
+                               // that take the steps in turn
   int32_t use_frozen;     // 0: no level of this context has a pinpoint cell; bit 1: a step needs the pinpoint rows (they are shown in the observation)
   uint8_t* obs;
   float* reward;
@@ -1243,9 +1245,14 @@ __device__ __forceinline__ void obs_wave_step(KArgs& a, const Lanes<S>& L, WaveM
 // The observation wavefront of a split rollout.  It needs nothing from the metrics wavefront: what
 // an observation shows -- the edited level, the agent's next cell, a restarted episode -- follows
 // from the loaded state, the seeds and the action stream alone, so this wavefront carries its own
-// copy of the level through all the steps and only writes observations.
-template <int S, int PROBLEM>
-__device__ __forceinline__ void obs_wave_rollout(const KArgs& a, const Lanes<S>& L, const WaveMap<S>& wm) {
+// copy of the level through all the steps and only writes observations.  Where the batch leaves
+// SIMDs idle, several such wavefronts take the steps in turn: this one writes the observations of
+// the steps t with (t & turn_mask) == turn and only follows the level through the others.
+// (TURNS = false is the same code for the launches in which every such wavefront writes every step:
+// the test per step costs the large batches 7 % through the registers it ties up.)
+template <int S, int PROBLEM, bool TURNS>
+__device__ __forceinline__ void obs_wave_rollout(const KArgs& a, const Lanes<S>& L, const WaveMap<S>& wm, int turn,
+                                                 int turn_mask) {
   using W = typename RowWord<S>::T;
   using PR = Prob<PROBLEM>;
   if (wm.env0 >= a.B) {  // the batch ends inside this workgroup: only the barrier is owed
@@ -1338,11 +1345,13 @@ __device__ __forceinline__ void obs_wave_rollout(const KArgs& a, const Lanes<S>&
         n_changes = 0;
       }
     }
-    if (fixed_plan) pl.base = base0 + slot_off;
-    else pl = obs_plan(a, L.lane, wm.sl, a.obs + slot_off, wm.env0, wm.nvalid);
+    if (!TURNS || (step & turn_mask) == turn) {
+      if (fixed_plan) pl.base = base0 + slot_off;
+      else pl = obs_plan(a, L.lane, wm.sl, a.obs + slot_off, wm.env0, wm.nvalid);
+      observe<S, PROBLEM, false, true>(a, L, wm, pl, p, fz, inside, qy, qx);
+    }
     slot = slot + 1 == a.obs_slots ? 0 : slot + 1;  // (step t writes slot t mod obs_slots)
     slot_off = slot == 0 ? 0 : slot_off + slot_bytes;
-    observe<S, PROBLEM, false, true>(a, L, wm, pl, p, fz, inside, qy, qx);
     py = qy;
     px = qx;
     act = act_next;
@@ -1374,10 +1383,15 @@ __device__ __forceinline__ void step_body(KArgs& a) {
     const int wid = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     if (wid != 0) {
       const int lg = a.envs_per_wave_log2 & 0xff, lgo = (a.envs_per_wave_log2 >> 8) & 0xff;
-      wm.init(a, L, nullptr, (level_group_of_block<ROLL>(ROLL ? a.by_die : 0) << (lg - lgo)) + wid - 1, lgo);
+      // (wavefronts 1 .. n of a rollout share out the levels of the group, the next n take the
+      // same levels at the next turn, and so on)
+      const int share = ROLL ? (wid - 1) & ((1 << (lg - lgo)) - 1) : wid - 1;
+      wm.init(a, L, nullptr, (level_group_of_block<ROLL>(ROLL ? a.by_die : 0) << (lg - lgo)) + share, lgo);
       if constexpr (ROLL) {
         wm.lds = lds_all + (wid - 1) * a.obs_lds_words;
-        obs_wave_rollout<S, PROBLEM>(a, L, wm);
+        const int turn_mask = (1 << ((a.envs_per_wave_log2 >> 16) & 0xff)) - 1;
+        if (turn_mask == 0) obs_wave_rollout<S, PROBLEM, false>(a, L, wm, 0, 0);
+        else obs_wave_rollout<S, PROBLEM, true>(a, L, wm, (wid - 1) >> (lg - lgo), turn_mask);
       } else {
         obs_wave_step<S, PROBLEM, PIN>(a, L, wm, lds_all, wid);
       }

@@ -74,7 +74,7 @@ def make_config(problem, batch, size, obs_w, *, min_size=None, pad_mode=PAD_BORD
                 probs=None, weights=None, target_lo=None, target_hi=None, max_w=None,
                 min_w=None, regions_mode=REGIONS_INCREMENTAL, levels_per_wave=0,
                 obs_store_mode=0, split_step=0, obs_format=0, pinpoint_tile=None, ctrl=None,
-                obs_frozen_channel=0, split_obs_levels=0, obs_pitch=0):
+                obs_frozen_channel=0, split_obs_levels=0, obs_pitch=0, rollout_turns=0):
     """ctrl: {metric index: (lo, hi)} -- targets drawn per episode; pinpoint_tile: tile of each
     pinpoint (-1 keeps the drawn one)."""
     w, lo, hi = default_reward_table(problem)
@@ -103,7 +103,7 @@ def make_config(problem, batch, size, obs_w, *, min_size=None, pad_mode=PAD_BORD
         ctrl_lo=[ctrl.get(i, (0, 0))[0] for i in range(16)],
         ctrl_hi=[ctrl.get(i, (0, 0))[1] for i in range(16)],
         obs_frozen_channel=obs_frozen_channel, split_obs_levels=split_obs_levels,
-        obs_pitch=obs_pitch,
+        obs_pitch=obs_pitch, rollout_turns=rollout_turns,
     )
 
 

@@ -363,7 +363,8 @@ def test_argument_errors_are_reported_not_raised_by_the_gpu():
     bad = wl.workload("maze16", batch=4)
     for field, val in (("obs_w", 64), ("max_h", 65), ("batch", 0), ("problem", 3), ("n_frozen", 9),
                        ("min_h", 17), ("max_steps", 0), ("pad_mode", 2), ("levels_per_wave", 5),
-                       ("split_step", 3), ("obs_store_mode", 4), ("split_obs_levels", 5)):
+                       ("split_step", 3), ("obs_store_mode", 4), ("split_obs_levels", 5),
+                       ("rollout_turns", 3)):
         with pytest.raises(binding.PcgrlError):
             binding.Pcgrl(dict(bad, **{field: val}), 0)
     env = binding.Pcgrl(bad, 0)
@@ -441,15 +442,18 @@ ROLLOUTS = [
 ]
 
 
-@pytest.mark.parametrize("split,olv", [(1, 0), (2, 0), (2, 1)], ids=["one-wavefront", "split", "split-obs1"])
+@pytest.mark.parametrize("split,olv,turns", [(1, 0, 0), (2, 0, 1), (2, 0, 0), (2, 1, 2)],
+                         ids=["one-wavefront", "split-one-turn", "split", "split-obs1-two-turns"])
 @pytest.mark.parametrize("label,cfg,T,slots", ROLLOUTS, ids=[r[0] for r in ROLLOUTS])
-def test_rollout_equals_the_same_steps_one_by_one(label, cfg, T, slots, split, olv):
+def test_rollout_equals_the_same_steps_one_by_one(label, cfg, T, slots, split, olv, turns):
     """pcgrl_rollout against the oracle stepped T times (every observation slot that survives,
     every reward and done flag, final state and metrics), with auto-resets inside the rollout, and
     against T calls of pcgrl_step.  split: the levels stay in one wavefront for the whole rollout,
-    or in a metrics wavefront and observation wavefronts that each carry their own copy."""
-    cfg = dict(cfg, split_step=split, split_obs_levels=olv)
-    print(f"[rollout] {label} T={T} slots={slots} split={split} obs levels={olv}", flush=True)
+    or in a metrics wavefront and observation wavefronts that each carry their own copy; turns:
+    how many observation wavefronts take the steps in turn (0: the library's choice, which at
+    these batches is as many as a workgroup holds)."""
+    cfg = dict(cfg, split_step=split, split_obs_levels=olv, rollout_turns=turns)
+    print(f"[rollout] {label} T={T} slots={slots} split={split} obs levels={olv} turns={turns}", flush=True)
     dev = torch.device("cuda", 0)
     B = cfg["batch"]
     acts_np = wl.random_actions(cfg, 8, T, bad_fraction=0.03)
@@ -743,6 +747,7 @@ def test_random_configurations_and_launch_shapes():
             levels_per_wave=int(rng.choice([0, 0, 1, 2, 4])), split_step=int(rng.choice([0, 0, 1, 2])),
             obs_store_mode=int(rng.choice([0, 0, 1, 2, 3])), obs_format=int(rng.choice([0, 0, 1])),
             obs_frozen_channel=int(rng.integers(0, 2)), split_obs_levels=int(rng.choice([0, 0, 1, 2])),
+            rollout_turns=int(rng.choice([0, 1, 2, 4])),
             weights=[float(v) for v in rng.uniform(-2, 4, size=16).astype(np.float32)] if rng.random() < 0.5 else None,
             ctrl={1: (3, 40)} if rng.random() < 0.3 else None)
         steps = 20 if batch * size * size < 3e6 else 8
@@ -775,7 +780,8 @@ def test_random_configurations_with_pitched_observations():
             max_steps=int(rng.choice([9, 1000])), autoreset=int(rng.integers(0, 2)),
             levels_per_wave=int(rng.choice([0, 0, 1, 2, 4])), split_step=int(rng.choice([0, 1, 2])),
             obs_store_mode=int(rng.choice([0, 1, 2, 3])), obs_format=packed, obs_frozen_channel=fzc,
-            split_obs_levels=int(rng.choice([0, 0, 1, 2])), obs_pitch=pitch)
+            split_obs_levels=int(rng.choice([0, 0, 1, 2])), obs_pitch=pitch,
+            rollout_turns=int(rng.choice([0, 1, 2, 4])))
         steps = 16 if batch * size * size < 3e6 else 8
         run_parity(cfg, steps, seed=int(rng.integers(1, 1000)), aseed=int(rng.integers(1, 1000)),
                    state_every=steps, label=f"random pitched configuration {n} (pitch {pitch}, {nbytes} bytes)")
