@@ -446,7 +446,7 @@ def main():
         out["rollout"] = dict(r, unit="env-steps/s",
                               roofline={"bound": "hbm", "achieved": r["achieved_GBs"], "peak": HBM_PEAK_GBS,
                                         "unit": "GB/s", "frac": r["frac"],
-                                        "kernel": "step_kernel<..., rollout>"})
+                                        "kernel": "rollout_kernel"})
         if attain:
             out["rollout"]["roofline"]["frac_attainable"] = r["achieved_GBs"] / attain["region_stores_rollout"]
 

@@ -761,6 +761,22 @@ __device__ __forceinline__ ObsPlan obs_plan(const KArgs& a, int lane, const Slot
   const bool packed = a.obs_packed != 0;
   pl.E = packed ? a.env_obs_bytes * 8 : a.env_obs_bytes;
   uint8_t* region = obs + (size_t)env0 * (size_t)a.env_obs_bytes;
+  // The usual case -- the array and the distance between two levels' observations are multiples
+  // of 16 bytes -- needs none of the edge arithmetic below (it runs on the scalar unit, which
+  // all the wavefronts of a compute unit share: thirty instructions fewer per wavefront).
+  if ((((uintptr_t)obs | (uintptr_t)(uint32_t)a.env_obs_bytes) & 15u) == 0) {
+    pl.dbytes = 0;
+    pl.base = region;
+    pl.d = 0;
+    pl.total = nvalid * pl.E;
+    pl.lane_off = sl.slot * pl.E + sl.copy * (a.obs_w * a.obs_w);
+    pl.active = sl.slot < nvalid;
+    pl.q_lo = 0;
+    pl.q_hi = (packed ? pl.total >> 3 : pl.total) >> 4;
+    pl.edge_pos = 0;
+    pl.edge_want = false;
+    return pl;
+  }
   pl.dbytes = (int)((uintptr_t)region & 15u);
   pl.base = region - pl.dbytes;
   pl.d = packed ? pl.dbytes * 8 : pl.dbytes;
@@ -783,6 +799,19 @@ __device__ __forceinline__ ObsPlan obs_plan(const KArgs& a, int lane, const Slot
 // to their uses, behind the wait for the loads).
 __device__ __forceinline__ void obs_plan_pin(ObsPlan& pl) {
   int ew = pl.edge_want ? 1 : 0, ac = pl.active ? 1 : 0;
+  // (wave-uniform values all of them; said explicitly, since a value that merges two branches may
+  // otherwise be given a vector register, which the constraints below cannot take)
+  {
+    const uintptr_t b = (uintptr_t)pl.base;
+    pl.base = (uint8_t*)(((uintptr_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(b >> 32)) << 32) |
+                         (uintptr_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)b));
+    pl.dbytes = __builtin_amdgcn_readfirstlane(pl.dbytes);
+    pl.d = __builtin_amdgcn_readfirstlane(pl.d);
+    pl.E = __builtin_amdgcn_readfirstlane(pl.E);
+    pl.total = __builtin_amdgcn_readfirstlane(pl.total);
+    pl.q_lo = __builtin_amdgcn_readfirstlane(pl.q_lo);
+    pl.q_hi = __builtin_amdgcn_readfirstlane(pl.q_hi);
+  }
   asm volatile("" : "+s"(pl.base), "+s"(pl.dbytes), "+s"(pl.d), "+s"(pl.E), "+s"(pl.total), "+s"(pl.q_lo),
                "+s"(pl.q_hi), "+v"(pl.lane_off), "+v"(pl.edge_pos), "+v"(ew), "+v"(ac));
   pl.edge_want = ew != 0;
