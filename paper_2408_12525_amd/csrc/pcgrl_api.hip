@@ -400,7 +400,10 @@ int pcgrl_create(pcgrl_ctx** out, const pcgrl_config* cfg, int device) {
   }
   // (the staging stream holds one bit per output byte, or per output bit when packed)
   const size_t stride_bits = cfg->obs_format == PCGRL_OBS_PACKED ? ctx->obs_stride * 8 : ctx->obs_stride;
-  auto lds_for = [&](int levels) { return ((8 * 15 + (size_t)levels * (stride_bits + 8) + 31) / 32 + 6) * 4; };
+  // (rounded up to whole 16-byte pieces: the kernels clear it 16 bytes per lane at a time)
+  auto lds_for = [&](int levels) {
+    return (((8 * 15 + (size_t)levels * (stride_bits + 8) + 31) / 32 + 6) * 4 + 15) / 16 * 16;
+  };
   ctx->lds_bytes = lds_for(ctx->epw);
   if (ctx->lds_bytes > 64 * 1024) {
     delete ctx;

@@ -817,9 +817,12 @@ __device__ __forceinline__ void obs_plan_pin(ObsPlan& pl) {
   pl.edge_want = ew != 0;
   pl.active = ac != 0;
 }
+// (16 bytes per lane and instruction: a wavefront's staging area is 16-byte aligned and a whole
+// number of 16-byte pieces long, see the library's sizing of it)
 __device__ __forceinline__ void obs_clear(uint32_t* lds, int lane, const ObsPlan& pl) {
-  const int nwords = (pl.total + 31) >> 5;
-  for (int i = lane; i < nwords; i += 64) lds[i] = 0;
+  const int npieces = (pl.total + 127) >> 7;
+  uint4* l4 = reinterpret_cast<uint4*>(__builtin_assume_aligned(lds, 16));
+  for (int i = lane; i < npieces; i += 64) l4[i] = make_uint4(0u, 0u, 0u, 0u);
 }
 
 // Writes the observations of this wavefront's levels.  WIDE = window wider than 32; CLEARED = the
@@ -1069,7 +1072,7 @@ template <int S, int PROBLEM>
 __global__ __launch_bounds__(64) void init_kernel(KArgs a) {
   using W = typename RowWord<S>::T;
   using PR = Prob<PROBLEM>;
-  extern __shared__ uint32_t lds_all[];
+  extern __shared__ __align__(16) uint32_t lds_all[];
   Lanes<S> L;
   WaveMap<S> wm;
   wm.init(a, L, lds_all, level_group_of_block<false>(0), a.envs_per_wave_log2 & 0xff);
@@ -1143,7 +1146,7 @@ template <int S, int PROBLEM>
 __global__ __launch_bounds__(64) void exact_diameter_kernel(KArgs a, int32_t* out, int parts_log2) {
   using W = typename RowWord<S>::T;
   using PR = Prob<PROBLEM>;
-  extern __shared__ uint32_t lds_all[];
+  extern __shared__ __align__(16) uint32_t lds_all[];
   Lanes<S> L;
   WaveMap<S> wm;
   const int part = (int)blockIdx.x & ((1 << parts_log2) - 1);
@@ -1399,7 +1402,7 @@ __device__ __forceinline__ void step_body(KArgs& a) {
   using PR = Prob<PROBLEM>;
   constexpr bool ROLL = MODE == kModeRollout || MODE == kModeRolloutSplit;
   constexpr bool SPLIT = MODE == kModeSplit || MODE == kModeRolloutSplit;
-  extern __shared__ uint32_t lds_all[];
+  extern __shared__ __align__(16) uint32_t lds_all[];
   Lanes<S> L;
   WaveMap<S> wm;
   wm.init(a, L, lds_all, level_group_of_block<ROLL>(ROLL ? a.by_die : 0), a.envs_per_wave_log2 & 0xff);
