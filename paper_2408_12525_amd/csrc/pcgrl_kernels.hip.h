@@ -18,6 +18,10 @@
 namespace pcgrl {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+// The same in the global address space: stores through a plain pointer whose origin the compiler
+// has lost sight of become flat instructions, which also count against the LDS counter.
+typedef __attribute__((address_space(1))) u32x4 global_u32x4;
+typedef __attribute__((address_space(1))) uint8_t global_u8;
 
 constexpr int kMaxMetrics = 16;
 
@@ -947,9 +951,12 @@ __device__ __forceinline__ void write_obs(const KArgs& a, const Lanes<S>& L, con
   if (a.obs_packed) {
     // bit-packed format: the stream itself is the output, 128 bits per aligned 16-byte chunk
     const uint4* lds128 = reinterpret_cast<const uint4*>(lds);
-    for (int q = pl.q_lo + L.lane; q < pl.q_hi; q += 64)
-      *reinterpret_cast<uint4*>(pl.base + ((uint32_t)q << 4)) = lds128[q];
-    if (pl.edge_want) pl.base[pl.edge_pos] = reinterpret_cast<const uint8_t*>(lds)[pl.edge_pos];
+    for (int q = pl.q_lo + L.lane; q < pl.q_hi; q += 64) {
+      const uint4 v = lds128[q];
+      const u32x4 nv = {v.x, v.y, v.z, v.w};
+      *(global_u32x4*)(pl.base + ((uint32_t)q << 4)) = nv;
+    }
+    if (pl.edge_want) *(global_u8*)(pl.base + pl.edge_pos) = reinterpret_cast<const uint8_t*>(lds)[pl.edge_pos];
     return;
   }
   const uint16_t* lds16 = reinterpret_cast<const uint16_t*>(lds);
@@ -979,14 +986,18 @@ __device__ __forceinline__ void write_obs(const KArgs& a, const Lanes<S>& L, con
     for (int q = pl.q_lo + L.lane; q < pl.q_hi; q += 64) {
       const uint4 v = widen(lds16[q]);
       u32x4 nv = {v.x, v.y, v.z, v.w};
-      __builtin_nontemporal_store(nv, reinterpret_cast<u32x4*>(pl.base + ((uint32_t)q << 4)));
+      __builtin_nontemporal_store(nv, (global_u32x4*)(pl.base + ((uint32_t)q << 4)));
     }
   } else {
-    for (int q = pl.q_lo + L.lane; q < pl.q_hi; q += 64)
-      *reinterpret_cast<uint4*>(pl.base + ((uint32_t)q << 4)) = widen(lds16[q]);
+    for (int q = pl.q_lo + L.lane; q < pl.q_hi; q += 64) {
+      const uint4 v = widen(lds16[q]);
+      const u32x4 nv = {v.x, v.y, v.z, v.w};
+      *(global_u32x4*)(pl.base + ((uint32_t)q << 4)) = nv;
+    }
   }
   // the partial chunk at the head (lanes 0-15, one byte each) and at the tail (lanes 16-31)
-  if (pl.edge_want) pl.base[pl.edge_pos] = (uint8_t)((lds16[pl.edge_pos >> 4] >> (pl.edge_pos & 15)) & 1u);
+  if (pl.edge_want)
+    *(global_u8*)(pl.base + pl.edge_pos) = (uint8_t)((lds16[pl.edge_pos >> 4] >> (pl.edge_pos & 15)) & 1u);
 }
 
 // ------------------------------------------------------------------ kernels
