@@ -873,9 +873,12 @@ __device__ __forceinline__ void write_obs(const KArgs& a, const Lanes<S>& L, con
         atomicOr(&lds[w0 + 1], (uint32_t)(lo >> 32));
         if (hi) atomicOr(&lds[w0 + 2], hi);
       } else {
+        // (both words unconditionally: a test for an empty upper half costs every lane a compare
+        // and the wavefront two scalar instructions, an OR of zero costs nothing that matters; the
+        // staging area has spare words behind the stream for the one that may fall past its end)
         uint64_t t = (uint64_t)bits << sh;
         atomicOr(&lds[w0], (uint32_t)t);
-        if ((uint32_t)(t >> 32)) atomicOr(&lds[w0 + 1], (uint32_t)(t >> 32));
+        atomicOr(&lds[w0 + 1], (uint32_t)(t >> 32));
       }
     };
     // One window row's channels, as far as they belong to this copy.  The copies of a level share
@@ -897,7 +900,11 @@ __device__ __forceinline__ void write_obs(const KArgs& a, const Lanes<S>& L, con
         if (j * COPIES <= 1 && 1 < (j + 1) * COPIES)  // the wall channel doubles as padding
           bits |= (!border && sl.copy == 1 - j * COPIES) ? pad_row : (BW)0;
         const bool mine = (j + 1) * COPIES <= PR::K || j * COPIES + sl.copy < PR::K;
-        if (mine && bits != 0) emit(off + j * COPIES * cstride, bits);
+        // (no test for an empty row: with a window of any size some lane of the wavefront nearly
+        // always has a tile of the kind, so the test only skipped work lane by lane, which costs
+        // the same as doing it: measured, 64x64 maze 15.37 -> 15.13 us per step, 32x32 dungeon
+        // 13.3 -> 12.9)
+        if (mine) emit(off + j * COPIES * cstride, bits);
       }
       if (border && sl.copy == (PR::K & (COPIES - 1)) && pad_row != 0)
         emit(off + (PR::K - sl.copy) * cstride, pad_row);
