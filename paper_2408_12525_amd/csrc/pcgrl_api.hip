@@ -106,14 +106,18 @@ inline uint32_t step_shape(const KArgs& a) {
          ((uint32_t)((a.envs_per_wave_log2 >> 8) & 0xff) << 27) | ((uint32_t)(a.use_frozen & 3) << 29);
 }
 #define PCGRL_STEP_ARGS(a) (a).planes, (a).frozen, (a).env, (a).metrics, (a).targets, (a).actions, step_shape(a), (a).plane_stride, (a)
-// (single steps come in two builds: with and without the code that looks pinpoint cells up)
+// (single steps come in three builds: windows of up to 32 cells with and without the code that looks
+// pinpoint cells up, and wider windows, with it)
 template <int S, int PROBLEM> struct LaunchStep {
   static int run(const pcgrl_ctx* ctx, const KArgs& a, hipStream_t st) {
-    if (a.use_frozen)
-      hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeStep, true>), dim3(ctx->nwaves), dim3(64), ctx->lds_bytes, st,
+    if (a.obs_w > 32)
+      hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeStep, true, true>), dim3(ctx->nwaves), dim3(64), ctx->lds_bytes, st,
+                         PCGRL_STEP_ARGS(a));
+    else if (a.use_frozen)
+      hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeStep, true, false>), dim3(ctx->nwaves), dim3(64), ctx->lds_bytes, st,
                          PCGRL_STEP_ARGS(a));
     else
-      hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeStep, false>), dim3(ctx->nwaves), dim3(64), ctx->lds_bytes, st,
+      hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeStep, false, false>), dim3(ctx->nwaves), dim3(64), ctx->lds_bytes, st,
                          PCGRL_STEP_ARGS(a));
     return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
   }
@@ -122,11 +126,14 @@ template <int S, int PROBLEM> struct LaunchSplit {  // a metrics wavefront and i
   static int run(const pcgrl_ctx* ctx, const KArgs& a, hipStream_t st) {
     const int obs_waves = ctx->split_m / ctx->split_o;
     const dim3 grid(ctx->split_groups), block(64 * (1 + obs_waves));
-    if (a.use_frozen)
-      hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeSplit, true>), grid, block, obs_waves * ctx->split_lds_wave, st,
+    if (a.obs_w > 32)
+      hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeSplit, true, true>), grid, block, obs_waves * ctx->split_lds_wave, st,
+                         PCGRL_STEP_ARGS(a));
+    else if (a.use_frozen)
+      hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeSplit, true, false>), grid, block, obs_waves * ctx->split_lds_wave, st,
                          PCGRL_STEP_ARGS(a));
     else
-      hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeSplit, false>), grid, block, obs_waves * ctx->split_lds_wave, st,
+      hipLaunchKernelGGL((step_kernel<S, PROBLEM, kModeSplit, false, false>), grid, block, obs_waves * ctx->split_lds_wave, st,
                          PCGRL_STEP_ARGS(a));
     return hipGetLastError() == hipSuccess ? PCGRL_OK : PCGRL_E_HIP;
   }
