@@ -1819,6 +1819,19 @@ __device__ __forceinline__ void step_body(KArgs& a) {
 // with its allocation, and then claims one register of the next block, which it never uses.
 template <int S, int PROBLEM, int MODE, bool PIN, bool WIDE> constexpr int kPadRegistersAbove = 0;
 template <> constexpr int kPadRegistersAbove<64, kMaze, kModeStep, true, true> = 64;
+// Makes the kernel's allocation reach past register N - 1 (a clobber the code never touches).
+template <int N> __device__ __forceinline__ void claim_register_above() {
+  static_assert(N == 0 || (N % 8 == 0 && N >= 40 && N <= 104), "an allocation is a multiple of eight registers");
+  if constexpr (N == 40) asm volatile("" ::: "v40");
+  if constexpr (N == 48) asm volatile("" ::: "v48");
+  if constexpr (N == 56) asm volatile("" ::: "v56");
+  if constexpr (N == 64) asm volatile("" ::: "v64");
+  if constexpr (N == 72) asm volatile("" ::: "v72");
+  if constexpr (N == 80) asm volatile("" ::: "v80");
+  if constexpr (N == 88) asm volatile("" ::: "v88");
+  if constexpr (N == 96) asm volatile("" ::: "v96");
+  if constexpr (N == 104) asm volatile("" ::: "v104");
+}
 template <int S, int PROBLEM, int MODE, bool PIN, bool WIDE>
 __global__ __launch_bounds__(MODE == kModeSplit ? 320 : 64) void step_kernel(
     void* planes_, void* frozen_, EnvRec* env_, int32_t* metrics_, uint32_t* targets_, const int32_t* actions_,
@@ -1837,9 +1850,7 @@ __global__ __launch_bounds__(MODE == kModeSplit ? 320 : 64) void step_kernel(
   a.plane_stride = plane_stride_;
   a.envs_per_wave_log2 = (int32_t)(((shape >> 25) & 3u) | (((shape >> 27) & 3u) << 8));
   a.use_frozen = (int32_t)((shape >> 29) & 3u);
-  constexpr int pad = kPadRegistersAbove<S, PROBLEM, MODE, PIN, WIDE>;
-  static_assert(pad == 0 || pad == 64, "add the clobber for this allocation");
-  if constexpr (pad == 64) asm volatile("" ::: "v64");
+  claim_register_above<kPadRegistersAbove<S, PROBLEM, MODE, PIN, WIDE>>();
   step_body<S, PROBLEM, MODE, PIN, WIDE ? kWidthWide : kWidthNarrow>(a);
 }
 
