@@ -788,6 +788,20 @@ def test_random_configurations_with_pitched_observations():
         _rollout_against_oracle(cfg, steps, int(rng.choice([1, 2, steps])), int(rng.integers(1, 1000)))
 
 
+@pytest.mark.parametrize("split", [1, 2], ids=["unsplit", "split"])
+@pytest.mark.parametrize("problem,size,ow,batch", [
+    (wl.MAZE, 47, 33, 2049), (wl.BINARY, 64, 63, 2049), (wl.DUNGEON, 64, 47, 2049),
+    (wl.BINARY, 32, 33, 4100), (wl.MAZE, 32, 47, 4100), (wl.DUNGEON, 23, 63, 4100), (wl.MAZE, 16, 33, 6000)])
+def test_wide_windows_with_every_simd_shared(problem, size, ow, batch, split):
+    """Windows wider than 32 cells run kernels of their own; at these batches several wavefronts
+    share every SIMD from the first launch on, which is the condition under which a kernel with a
+    register allocation the hardware mishandles gives wrong observations in a few percent of the
+    levels (the build checks for the instruction pattern; this checks the result)."""
+    cfg = wl.make_config(problem, batch, size, ow, pad_mode=wl.PAD_BORDER, n_frozen=1, max_steps=1000,
+                         split_step=split, obs_store_mode=1)
+    run_parity(cfg, 4, seed=132, aseed=546, state_every=4, label=f"wide window {ow} on {size}x{size}, batch {batch}")
+
+
 def test_pinpoints_installed_later_are_respected():
     """A context created without pinpoints runs the step kernels that carry no pinpoint code; once
     pcgrl_set_state installs a frozen mask, steps (and a rollout) must leave those cells alone."""
